@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the failure-remapped MoE layer on one MI355X.
+
+A step is one pass of the whole hot path (route -> dispatch -> expert FFN -> combine) over one
+batch of synthetic tokens, with the workload's failed ranks removed from the expert map, replayed
+from one captured graph.  Prints one JSON line:
+
+  value        tokens/s of the layer (T / mean step time), inputs resident in HBM
+  roofline     the dominant kernel (grouped gate/up GEMM of the routed experts) against the bf16
+               dense MFMA peak, from HIP-event timing of that kernel inside this run
+  cpu_baseline the CPU oracle timed on this host on a bounded sample of the same workload
+  stages       per-kernel mean microseconds and the stage rates (GB/s, TFLOP/s)
+  remap        latency from revive_update_map to the end of the first step under the new map,
+               replaying the same graph executable
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "fp32": 157.3}
+
+
+def algorithmic_work(cfg):
+    """Algorithmic bytes / flops per step of each stage (read every input once, write every output once)."""
+    b = 2 if cfg.dtype == "bf16" else 4
+    T, H, E, k, I, Is = cfg.T, cfg.H, cfg.E, cfg.k, cfg.I, cfg.I_shared
+    N = T * k
+    return {
+        "route_bytes": T * H * b + H * E * b + T * k * 12,
+        "dispatch_bytes": (T + N) * H * b + N * 16,
+        "combine_bytes": (N + (2 if Is else 1) * T) * H * b + N * 8,
+        "gate_up_flops": 4 * N * H * I,
+        "down_flops": 2 * N * H * I,
+        "shared_gate_up_flops": 4 * T * H * Is,
+        "shared_down_flops": 2 * T * H * Is,
+    }
+
+
+def cpu_baseline(cfg, g, sample_tokens):
+    """Time the oracle (as it stands) on the first `sample_tokens` tokens of the workload."""
+    import numpy as np
+    import torch
+    from oracle import revive_oracle as orc
+
+    def f64(t):
+        return t.detach().cpu().to(torch.float64).numpy()
+
+    x = f64(g.x[:sample_tokens])
+    w_r = f64(g.w_router)
+    experts = {}
+    for e in range(cfg.E):
+        p = int(np.nonzero(g.p2l == e)[0][0])
+        gu = f64(g.gu[p])
+        experts[e] = {"gate": np.ascontiguousarray(gu[:cfg.I].T), "up": np.ascontiguousarray(gu[cfg.I:].T),
+                      "down": np.ascontiguousarray(f64(g.dn[p]).T)}
+    shared = None
+    if g.sh_gate_up is not None:
+        gu = f64(g.sh_gate_up)
+        shared = {"gate": np.ascontiguousarray(gu[:cfg.I_shared].T), "up": np.ascontiguousarray(gu[cfg.I_shared:].T),
+                  "down": np.ascontiguousarray(f64(g.sh_down).T)}
+    emap = orc.build_map(g.p2l, g.failed, cfg.slots_per_rank, cfg.E, cfg.max_replicas)
+    t0 = time.perf_counter()
+    orc.layer_staged(x, w_r, experts, shared, g.p2l, emap, cfg.k, cfg.score_fn, cfg.n_group, cfg.topk_group)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    return {"value": sample_tokens / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"first {sample_tokens} of {cfg.T} tokens, whole layer (route, dispatch, fp64 expert FFN over all "
+                      f"{cfg.E} experts' weights, combine), {dt:.2f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c2", help="c2 (default, the metric's configuration), c3, c4, c5, c1")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=512)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (expert-parallel ranks are simulated as rank segments "
+              "inside one HBM); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth
+    from paper_2602_21140_amd.layer import ResidentLayer
+
+    cfg = synth.get_config(args.workload)
+    torch.cuda.set_device(0)
+    g = ResidentLayer(cfg, device="cuda:0")
+    L = g.layer
+    work = algorithmic_work(cfg)
+    stream = torch.cuda.Stream()
+    K, W = args.steps, args.warmup
+
+    with torch.cuda.stream(stream):
+        g.forward(stream=stream)                      # eager pass (also configures the kernels)
+        stream.synchronize()
+        g.capture(stream)
+        exec_id = L.graph_exec_id(g.graph)
+        for _ in range(W):
+            g.replay(stream)
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(K):
+            g.replay(stream)
+        e1.record(stream)
+        stream.synchronize()
+        ms_per_step = e0.elapsed_time(e1) / K
+
+        # per-kernel HIP-event timing of the same step, launched eagerly on the same stream
+        L.set_kernel_timing(True)
+        L.reset_kernel_times()
+        for _ in range(K):
+            g.forward(stream=stream)
+        stream.synchronize()
+        times = L.kernel_times()
+        L.set_kernel_timing(False)
+
+        # recovery: flip the mask, replay the same executable, time to the end of the first new step
+        other = [r for r in range(cfg.n_ranks) if r not in cfg.failed_ranks]
+        new_failed = list(cfg.failed_ranks[:-1]) + [other[len(other) // 2]] if cfg.failed_ranks else [other[0]]
+        try_failed = new_failed if args.workload != "c5" else []
+        remap = []
+        for trial in range(5):
+            target = try_failed if trial % 2 == 0 else list(cfg.failed_ranks)
+            stream.synchronize()
+            t0 = time.perf_counter()
+            g.set_failed(target, stream=stream)
+            t1 = time.perf_counter()
+            g.replay(stream)
+            stream.synchronize()
+            t2 = time.perf_counter()
+            phys = g.buf["topk_phys"]
+            dead = torch.from_numpy(np.repeat(g.failed, cfg.slots_per_rank)).to(phys.device)
+            ok = not bool(dead[phys.long()].any().item())
+            remap.append(((t1 - t0) * 1e3, (t2 - t0) * 1e3, ok))
+        g.set_failed(cfg.failed_ranks, stream=stream)
+        stream.synchronize()
+        same_exec = L.graph_exec_id(g.graph) == exec_id
+
+    avg_us = {n: (1e3 * ms / c if c else None) for n, (ms, c) in times.items()}
+    dom = "ffn_gate_up"
+    dom_tflops = work["gate_up_flops"] / (avg_us[dom] * 1e-6) / 1e12
+    peak = MFMA_PEAK_TFLOPS[cfg.dtype]
+
+    def gbs(nbytes, names):
+        us = sum(avg_us[n] for n in names if avg_us[n])
+        return nbytes / (us * 1e-6) / 1e9 if us else None
+
+    ffn_names = ["ffn_tiles", "ffn_gate_up", "ffn_down", "ffn_shared_gate_up", "ffn_shared_down"]
+    ffn_us = sum(avg_us[n] for n in ffn_names if avg_us[n])
+    ffn_flops = sum(work[n] for n in ("gate_up_flops", "down_flops", "shared_gate_up_flops", "shared_down_flops"))
+    stages = {
+        "kernel_us": {n: (round(v, 2) if v else None) for n, v in avg_us.items()},
+        "route_GBs": gbs(work["route_bytes"], ["router_gemm", "route_topk"]),
+        "dispatch_GBs": gbs(work["dispatch_bytes"], ["dispatch_count", "dispatch_scan", "dispatch_place", "dispatch_permute"]),
+        "dispatch_frac_of_hbm": None,
+        "combine_GBs": gbs(work["combine_bytes"], ["combine"]),
+        "ffn_TFLOPs": ffn_flops / (ffn_us * 1e-6) / 1e12,
+        "ffn_frac_of_mfma_peak": ffn_flops / (ffn_us * 1e-6) / 1e12 / peak,
+        "sum_kernel_us": round(sum(v for v in avg_us.values() if v), 1),
+    }
+    stages["dispatch_frac_of_hbm"] = stages["dispatch_GBs"] / HBM_PEAK_GBS
+    stages["combine_frac_of_hbm"] = stages["combine_GBs"] / HBM_PEAK_GBS
+    host_ms = sorted(r[0] for r in remap)[len(remap) // 2]
+    first_ms = sorted(r[1] for r in remap)[len(remap) // 2]
+
+    result = {
+        "metric": "MoE-layer tokens/s with failed ranks", "value": cfg.T / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={cfg.T} H={cfg.H} E={cfg.E} top-{cfg.k} I={cfg.I} shared I={cfg.I_shared} "
+                               f"{cfg.score_fn}" + (f" {cfg.n_group} groups/top-{cfg.topk_group}" if cfg.n_group > 1 else "")
+                               + f", {cfg.n_ranks} simulated ranks x {cfg.slots_per_rank} slots, failed ranks "
+                               f"{list(cfg.failed_ranks)}",
+                   "map": g.stats, "execution": "one captured graph replayed per step"},
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel<SwiGLU> (ffn_gate_up)" if cfg.dtype == "bf16" else "gemm_f32_kernel<SwiGLU>",
+                     "achieved": dom_tflops, "peak": peak, "unit": "TFLOP/s", "frac": dom_tflops / peak,
+                     "avg_launch_us": avg_us[dom], "flops_per_launch": work["gate_up_flops"], "traffic": None},
+        "stages": stages,
+        "remap": {"update_map_host_ms": host_ms, "update_to_first_step_done_ms": first_ms,
+                  "minus_steady_step_ms": first_ms - ms_per_step, "routes_avoid_failed_ranks": all(r[2] for r in remap),
+                  "same_graph_exec": same_exec},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, g, min(args.cpu_sample_tokens, cfg.T))
+    g.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

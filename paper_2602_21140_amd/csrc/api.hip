@@ -1,0 +1,470 @@
+// Context, map update (recovery step), graph replay and timing of the failure-remapped MoE layer.
+#include <algorithm>
+#include <new>
+
+#include "ctx.hpp"
+
+namespace revive {
+
+static thread_local std::string g_noctx_error;
+
+int fail(const revive_ctx* ctx, int status, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  if (ctx) ctx->err = buf; else g_noctx_error = buf;
+  return status;
+}
+
+int check_hip(const revive_ctx* ctx, hipError_t e, const char* what) {
+  if (e == hipSuccess) return REVIVE_OK;
+  return fail(ctx, REVIVE_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+KernelTimer::KernelTimer(revive_ctx* c, int kernel, hipStream_t s) : ctx(c), stream(s) {
+  if (!ctx->timing) return;
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &st) != hipSuccess || st != hipStreamCaptureStatusNone) return;
+  if (ctx->slots_used == ctx->slots.size()) fold_timing(ctx);
+  slot = &ctx->slots[ctx->slots_used++];
+  slot->kernel = kernel;
+  (void)hipEventRecord(slot->start, s);
+}
+
+KernelTimer::~KernelTimer() {
+  if (slot) (void)hipEventRecord(slot->stop, stream);
+}
+
+int fold_timing(revive_ctx* ctx) {
+  for (size_t i = 0; i < ctx->slots_used; ++i) {
+    TimingSlot& s = ctx->slots[i];
+    REVIVE_HIP(ctx, hipEventSynchronize(s.stop));
+    float ms = 0.f;
+    REVIVE_HIP(ctx, hipEventElapsedTime(&ms, s.start, s.stop));
+    ctx->time_ms[s.kernel] += ms;
+    ctx->time_n[s.kernel] += 1;
+  }
+  ctx->slots_used = 0;
+  return REVIVE_OK;
+}
+
+// Worst case over all possible logits: can a token always be given k live experts?
+// Ungrouped: at least k live experts.  Grouped: a group without live experts is kept only when
+// fewer than topk_group groups have one, so the worst kept set is the topk_group live groups
+// with the fewest live experts (or every live group when there are fewer than that).
+static bool enough_live(const revive_config& c, const int32_t* count) {
+  if (c.n_group <= 1) {
+    int live = 0;
+    for (int e = 0; e < c.E; ++e) live += count[e] > 0;
+    return live >= c.k;
+  }
+  const int gsz = c.E / c.n_group;
+  std::vector<int> per;
+  for (int g = 0; g < c.n_group; ++g) {
+    int live = 0;
+    for (int e = g * gsz; e < (g + 1) * gsz; ++e) live += count[e] > 0;
+    if (live > 0) per.push_back(live);
+  }
+  std::sort(per.begin(), per.end());
+  int reach = 0;
+  for (size_t i = 0; i < per.size() && i < static_cast<size_t>(c.topk_group); ++i) reach += per[i];
+  return reach >= c.k;
+}
+
+// Host construction of the map tables from the static placement and the failed-rank bytes.
+// Writes count[E], table[E * max_replicas] (-1 padded) and alive[P]; all three must be zeroed by
+// the caller except table, which is filled here.  `who` receives the error text (may be null).
+static int build_tables(const revive_ctx* who, const revive_config& c, const int32_t* p2l, const uint8_t* rank_failed,
+                        int32_t* count, int32_t* table, uint8_t* alive, revive_map_stats* stats) {
+  const int P = c.n_ranks * c.slots_per_rank;
+  for (int r = 0; r < c.n_ranks; ++r)
+    if (rank_failed[r] > 1) return fail(who, REVIVE_EINVAL, "rank_failed[%d] = %d is not 0 or 1", r, rank_failed[r]);
+  std::vector<int32_t> full(c.E, 0);
+  std::fill(count, count + c.E, 0);
+  std::fill(alive, alive + P, 0);
+  std::fill(table, table + static_cast<size_t>(c.E) * c.max_replicas, -1);
+  revive_map_stats st{0, 0, 0, 0};
+  for (int p = 0; p < P; ++p) {  // ascending p => each expert's list is ascending
+    const int32_t e = p2l[p];
+    if (e < -1 || e >= c.E) return fail(who, REVIVE_EINVAL, "slot %d holds expert %d, outside [-1, %d)", p, e, c.E);
+    if (e < 0) continue;
+    if (++full[e] > c.max_replicas) return fail(who, REVIVE_EINVAL, "expert %d has more than max_replicas = %d copies", e, c.max_replicas);
+    if (rank_failed[p / c.slots_per_rank]) continue;
+    alive[p] = 1;
+    table[static_cast<size_t>(e) * c.max_replicas + count[e]++] = p;
+    ++st.n_live_slots;
+  }
+  for (int e = 0; e < c.E; ++e) {
+    if (count[e] == 0) ++st.n_lost_experts;
+    else {
+      ++st.n_live_experts;
+      if (count[e] < full[e]) ++st.n_degraded_experts;
+    }
+  }
+  if (stats) *stats = st;
+  if (!enough_live(c, count))
+    return fail(who, REVIVE_EINSUFFICIENT_EXPERTS, "only %d live experts; a token could not be given k = %d of them",
+                st.n_live_experts, c.k);
+  return REVIVE_OK;
+}
+
+static int check_config(const revive_config& c) {
+  const int64_t P = static_cast<int64_t>(c.n_ranks) * c.slots_per_rank;
+  if (c.T_max < 0 || c.H <= 0 || c.E <= 0 || c.k <= 0 || c.I <= 0 || c.I_shared < 0 || c.n_ranks <= 0 ||
+      c.slots_per_rank <= 0 || c.max_replicas <= 0)
+    return fail(nullptr, REVIVE_EINVAL, "config: sizes must be positive");
+  if (c.E > kMaxE || P > kMaxP || c.k > kMaxK || c.k > c.E)
+    return fail(nullptr, REVIVE_EINVAL, "config: E <= %d, P <= %d, k <= min(%d, E) required", kMaxE, kMaxP, kMaxK);
+  if (c.dtype != REVIVE_DTYPE_F32 && c.dtype != REVIVE_DTYPE_BF16)
+    return fail(nullptr, REVIVE_EINVAL, "config: dtype must be 0 (fp32) or 1 (bf16)");
+  if (c.score_fn != REVIVE_SCORE_SOFTMAX && c.score_fn != REVIVE_SCORE_SIGMOID)
+    return fail(nullptr, REVIVE_EINVAL, "config: unknown score_fn");
+  if (c.n_group < 1 || c.topk_group < 1 || c.topk_group > c.n_group || c.E % c.n_group != 0 || c.n_group > 32)
+    return fail(nullptr, REVIVE_EINVAL, "config: need 1 <= topk_group <= n_group <= 32 and n_group | E");
+  if (c.H % 8 != 0) return fail(nullptr, REVIVE_EINVAL, "config: H must be a multiple of 8");
+  if (c.dtype == REVIVE_DTYPE_BF16 && (c.H % 64 != 0 || c.I % 64 != 0 || c.I_shared % 64 != 0))
+    return fail(nullptr, REVIVE_EINVAL, "config: bf16 needs H, I and I_shared multiples of 64");
+  if (c.dtype == REVIVE_DTYPE_F32 && (c.I % 4 != 0 || c.I_shared % 4 != 0))
+    return fail(nullptr, REVIVE_EINVAL, "config: fp32 needs I and I_shared multiples of 4");
+  if (static_cast<int64_t>(c.T_max) * c.k >= (1ll << 30)) return fail(nullptr, REVIVE_EINVAL, "config: T_max * k too large");
+  return REVIVE_OK;
+}
+
+}  // namespace revive
+
+using namespace revive;
+
+extern "C" {
+
+int revive_create(const revive_config* cfg, revive_ctx** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !out) return fail(nullptr, REVIVE_EINVAL, "revive_create: null argument");
+  const revive_config& c = *cfg;
+  const int64_t P = static_cast<int64_t>(c.n_ranks) * c.slots_per_rank;
+  {
+    int rc = check_config(c);
+    if (rc != REVIVE_OK) return rc;
+  }
+
+  revive_ctx* ctx = new (std::nothrow) revive_ctx();
+  if (!ctx) return fail(nullptr, REVIVE_ENOMEM, "revive_create: out of host memory");
+  ctx->cfg = c;
+  ctx->P = static_cast<int>(P);
+  ctx->elem = c.dtype == REVIVE_DTYPE_BF16 ? 2 : 4;
+
+  MapLayout& m = ctx->map;
+  m.off_count = 0;
+  m.off_table = align_up(m.off_count + sizeof(int32_t) * c.E, 16);
+  m.off_alive = align_up(m.off_table + sizeof(int32_t) * c.E * c.max_replicas, 16);
+  m.bytes = align_up(m.off_alive + static_cast<size_t>(P), 16);
+
+  const int64_t N_max = static_cast<int64_t>(c.T_max) * c.k;
+  const int tile_m = c.dtype == REVIVE_DTYPE_BF16 ? kTileM_bf16 : kTileM_f32;
+  Workspace& w = ctx->ws;
+  size_t off = 0;
+  w.off_block_hist = off;
+  off = align_up(off + sizeof(int32_t) * std::max<int64_t>(1, ceil_div(static_cast<int>(N_max), kDispatchChunk)) * P, 256);
+  w.off_tiles = off;
+  off = align_up(off + sizeof(MTile) * max_tiles(N_max, static_cast<int>(P), tile_m), 256);
+  w.off_tile_count = off;
+  off = align_up(off + 4 * sizeof(int32_t), 256);
+  w.off_h = off;
+  off = align_up(off + ctx->elem * N_max * c.I, 256);
+  w.off_h_shared = off;
+  off = align_up(off + ctx->elem * static_cast<size_t>(c.T_max) * c.I_shared, 256);
+  w.bytes = off;
+
+  int rc = check_hip(nullptr, hipGetDevice(&ctx->device), "hipGetDevice");
+  if (rc == REVIVE_OK) rc = check_hip(nullptr, hipMalloc(reinterpret_cast<void**>(&ctx->d_map), m.bytes), "hipMalloc(map)");
+  if (rc == REVIVE_OK) rc = check_hip(nullptr, hipMemset(ctx->d_map, 0, m.bytes), "hipMemset(map)");
+  if (rc == REVIVE_OK)
+    rc = check_hip(nullptr, hipMalloc(reinterpret_cast<void**>(&ctx->d_phys_to_logical), sizeof(int32_t) * P), "hipMalloc(p2l)");
+  for (int i = 0; i < 2 && rc == REVIVE_OK; ++i) {
+    rc = check_hip(nullptr, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_stage[i]), m.bytes, hipHostMallocDefault), "hipHostMalloc");
+    if (rc == REVIVE_OK) rc = check_hip(nullptr, hipEventCreateWithFlags(&ctx->stage_done[i], hipEventDisableTiming), "hipEventCreate");
+  }
+  if (rc != REVIVE_OK) {
+    revive_destroy(ctx);
+    return rc;
+  }
+  ctx->host_blob.assign(m.bytes, 0);
+  *out = ctx;
+  return REVIVE_OK;
+}
+
+int revive_destroy(revive_ctx* ctx) {
+  if (!ctx) return REVIVE_OK;
+  for (int i = 0; i < 2; ++i) {
+    if (ctx->stage_done[i]) {
+      if (ctx->stage_used[i]) (void)hipEventSynchronize(ctx->stage_done[i]);
+      (void)hipEventDestroy(ctx->stage_done[i]);
+    }
+    if (ctx->h_stage[i]) (void)hipHostFree(ctx->h_stage[i]);
+  }
+  for (auto& s : ctx->slots) {
+    (void)hipEventDestroy(s.start);
+    (void)hipEventDestroy(s.stop);
+  }
+  if (ctx->d_map) (void)hipFree(ctx->d_map);
+  if (ctx->d_phys_to_logical) (void)hipFree(ctx->d_phys_to_logical);
+  delete ctx;
+  return REVIVE_OK;
+}
+
+int revive_workspace_bytes(const revive_ctx* ctx, size_t* bytes) {
+  if (!ctx || !bytes) return fail(ctx, REVIVE_EINVAL, "revive_workspace_bytes: null argument");
+  *bytes = ctx->ws.bytes;
+  return REVIVE_OK;
+}
+
+int revive_bind_workspace(revive_ctx* ctx, void* dev, size_t bytes) {
+  if (!ctx || !dev) return fail(ctx, REVIVE_EINVAL, "revive_bind_workspace: null argument");
+  if (bytes < ctx->ws.bytes) return fail(ctx, REVIVE_ENOMEM, "revive_bind_workspace: %zu bytes given, %zu needed", bytes, ctx->ws.bytes);
+  if (reinterpret_cast<uintptr_t>(dev) % 256 != 0) return fail(ctx, REVIVE_EINVAL, "revive_bind_workspace: buffer must be 256-byte aligned");
+  ctx->d_ws = static_cast<uint8_t*>(dev);
+  ctx->ws_bound = bytes;
+  return REVIVE_OK;
+}
+
+int revive_set_placement(revive_ctx* ctx, const int32_t* phys_to_logical) {
+  if (!ctx || !phys_to_logical) return fail(ctx, REVIVE_EINVAL, "revive_set_placement: null argument");
+  const revive_config& c = ctx->cfg;
+  std::vector<int32_t> full(c.E, 0);
+  for (int p = 0; p < ctx->P; ++p) {
+    const int32_t e = phys_to_logical[p];
+    if (e < -1 || e >= c.E) return fail(ctx, REVIVE_EINVAL, "revive_set_placement: slot %d holds expert %d, outside [-1, %d)", p, e, c.E);
+    if (e >= 0 && ++full[e] > c.max_replicas)
+      return fail(ctx, REVIVE_EINVAL, "revive_set_placement: expert %d has more than max_replicas = %d copies", e, c.max_replicas);
+  }
+  ctx->phys_to_logical.assign(phys_to_logical, phys_to_logical + ctx->P);
+  ctx->full_count = full;
+  REVIVE_HIP(ctx, hipMemcpy(ctx->d_phys_to_logical, phys_to_logical, sizeof(int32_t) * ctx->P, hipMemcpyHostToDevice));
+  ctx->placement_set = true;
+  ctx->map_set = false;
+  return REVIVE_OK;
+}
+
+int revive_update_map(revive_ctx* ctx, const uint8_t* rank_failed, revive_stream stream, revive_map_stats* stats) {
+  if (!ctx || !rank_failed) return fail(ctx, REVIVE_EINVAL, "revive_update_map: null argument");
+  if (!ctx->placement_set) return fail(ctx, REVIVE_ESTATE, "revive_update_map: call revive_set_placement first");
+  const revive_config& c = ctx->cfg;
+
+  // Build the new tables aside; nothing is committed until validation has passed.
+  std::vector<uint8_t> blob(ctx->map.bytes, 0);
+  revive_map_stats st{0, 0, 0, 0};
+  int rc = build_tables(ctx, c, ctx->phys_to_logical.data(), rank_failed,
+                        reinterpret_cast<int32_t*>(blob.data() + ctx->map.off_count),
+                        reinterpret_cast<int32_t*>(blob.data() + ctx->map.off_table), blob.data() + ctx->map.off_alive, &st);
+  if (rc != REVIVE_OK) return rc;
+
+  const int b = ctx->stage_next;
+  if (ctx->stage_used[b]) REVIVE_HIP(ctx, hipEventSynchronize(ctx->stage_done[b]));  // previous copy from this buffer
+  std::memcpy(ctx->h_stage[b], blob.data(), blob.size());
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  REVIVE_HIP(ctx, hipMemcpyAsync(ctx->d_map, ctx->h_stage[b], blob.size(), hipMemcpyHostToDevice, s));
+  REVIVE_HIP(ctx, hipEventRecord(ctx->stage_done[b], s));
+  ctx->stage_used[b] = true;
+  ctx->stage_next = b ^ 1;
+  ctx->host_blob.swap(blob);
+  ctx->map_set = true;
+  if (stats) *stats = st;
+  return REVIVE_OK;
+}
+
+int revive_get_map(const revive_ctx* ctx, int32_t* l2p_table, int32_t* l2p_count, uint8_t* slot_alive) {
+  if (!ctx) return fail(ctx, REVIVE_EINVAL, "revive_get_map: null context");
+  if (!ctx->map_set) return fail(ctx, REVIVE_ESTATE, "revive_get_map: no map has been built yet");
+  const revive_config& c = ctx->cfg;
+  if (l2p_count) std::memcpy(l2p_count, ctx->host_blob.data() + ctx->map.off_count, sizeof(int32_t) * c.E);
+  if (l2p_table) std::memcpy(l2p_table, ctx->host_blob.data() + ctx->map.off_table, sizeof(int32_t) * c.E * c.max_replicas);
+  if (slot_alive) std::memcpy(slot_alive, ctx->host_blob.data() + ctx->map.off_alive, ctx->P);
+  return REVIVE_OK;
+}
+
+int revive_build_map(const revive_config* cfg, const int32_t* phys_to_logical, const uint8_t* rank_failed,
+                     int32_t* l2p_table, int32_t* l2p_count, uint8_t* slot_alive, revive_map_stats* stats) {
+  if (!cfg || !phys_to_logical || !rank_failed || !l2p_table || !l2p_count || !slot_alive)
+    return fail(nullptr, REVIVE_EINVAL, "revive_build_map: null argument");
+  int rc = check_config(*cfg);
+  if (rc != REVIVE_OK) return rc;
+  return build_tables(nullptr, *cfg, phys_to_logical, rank_failed, l2p_count, l2p_table, slot_alive, stats);
+}
+
+// ---- data path entry points: argument checks, then the stage's launcher ----
+
+static int check_call(revive_ctx* ctx, const char* who, int32_t T, bool need_ws) {
+  if (!ctx) return fail(ctx, REVIVE_EINVAL, "%s: null context", who);
+  if (T < 0 || T > ctx->cfg.T_max) return fail(ctx, REVIVE_EINVAL, "%s: T = %d outside [0, T_max = %d]", who, T, ctx->cfg.T_max);
+  if (need_ws && !ctx->d_ws) return fail(ctx, REVIVE_ESTATE, "%s: no workspace bound", who);
+  return REVIVE_OK;
+}
+
+int revive_route(revive_ctx* ctx, const void* x, const void* w_router, float* logits, int32_t logits_given, int32_t T,
+                 int32_t* topk_logical, float* topk_weight, int32_t* topk_phys, revive_stream stream) {
+  int rc = check_call(ctx, "revive_route", T, false);
+  if (rc != REVIVE_OK) return rc;
+  if (!ctx->map_set) return fail(ctx, REVIVE_ESTATE, "revive_route: call revive_update_map first");
+  if (!logits || !topk_logical || !topk_weight || !topk_phys) return fail(ctx, REVIVE_EINVAL, "revive_route: null output or logits");
+  if (!logits_given && (!x || !w_router)) return fail(ctx, REVIVE_EINVAL, "revive_route: x and w_router are required unless logits are given");
+  if (T == 0) return REVIVE_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!logits_given) {
+    rc = launch_router_gemm(ctx, x, w_router, logits, T, s);
+    if (rc != REVIVE_OK) return rc;
+  }
+  return launch_route_topk(ctx, logits, T, topk_logical, topk_weight, topk_phys, s);
+}
+
+int revive_dispatch(revive_ctx* ctx, const void* x, const int32_t* topk_phys, int32_t T, void* x_perm,
+                    int32_t* slot_offsets, int32_t* dst_row, int32_t* src_of, revive_stream stream) {
+  int rc = check_call(ctx, "revive_dispatch", T, true);
+  if (rc != REVIVE_OK) return rc;
+  if (!slot_offsets) return fail(ctx, REVIVE_EINVAL, "revive_dispatch: null slot_offsets");
+  if (T > 0 && (!x || !topk_phys || !x_perm || !dst_row || !src_of)) return fail(ctx, REVIVE_EINVAL, "revive_dispatch: null argument");
+  return launch_dispatch(ctx, x, topk_phys, T, x_perm, slot_offsets, dst_row, src_of, static_cast<hipStream_t>(stream));
+}
+
+int revive_expert_ffn(revive_ctx* ctx, const void* x_perm, const int32_t* slot_offsets, const void* const* w_gate_up,
+                      const void* const* w_down, void* y_perm, const void* x, const void* w_sh_gate_up,
+                      const void* w_sh_down, void* y_shared, int32_t T, revive_stream stream) {
+  int rc = check_call(ctx, "revive_expert_ffn", T, true);
+  if (rc != REVIVE_OK) return rc;
+  if (T == 0) return REVIVE_OK;
+  if (!x_perm || !slot_offsets || !w_gate_up || !w_down || !y_perm) return fail(ctx, REVIVE_EINVAL, "revive_expert_ffn: null argument");
+  if (y_shared) {
+    if (ctx->cfg.I_shared == 0) return fail(ctx, REVIVE_EINVAL, "revive_expert_ffn: y_shared given but the layer has no shared expert");
+    if (!x || !w_sh_gate_up || !w_sh_down) return fail(ctx, REVIVE_EINVAL, "revive_expert_ffn: shared expert needs x and both weight matrices");
+  }
+  return launch_expert_ffn(ctx, x_perm, slot_offsets, w_gate_up, w_down, y_perm, x, w_sh_gate_up, w_sh_down, y_shared, T,
+                           static_cast<hipStream_t>(stream));
+}
+
+int revive_combine(revive_ctx* ctx, const void* y_perm, const int32_t* dst_row, const float* topk_weight,
+                   const void* y_shared, int32_t T, void* out, revive_stream stream) {
+  int rc = check_call(ctx, "revive_combine", T, false);
+  if (rc != REVIVE_OK) return rc;
+  if (T == 0) return REVIVE_OK;
+  if (!y_perm || !dst_row || !topk_weight || !out) return fail(ctx, REVIVE_EINVAL, "revive_combine: null argument");
+  return launch_combine(ctx, y_perm, dst_row, topk_weight, y_shared, T, out, static_cast<hipStream_t>(stream));
+}
+
+// ---- graph replay ----
+
+}  // extern "C"
+
+struct revive_graph {
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+};
+
+extern "C" {
+
+int revive_graph_begin(revive_ctx* ctx, revive_stream stream) {
+  if (!ctx) return fail(ctx, REVIVE_EINVAL, "revive_graph_begin: null context");
+  if (!stream) return fail(ctx, REVIVE_EINVAL, "revive_graph_begin: the default stream cannot be captured");
+  REVIVE_HIP(ctx, hipStreamBeginCapture(static_cast<hipStream_t>(stream), hipStreamCaptureModeRelaxed));
+  return REVIVE_OK;
+}
+
+int revive_graph_end(revive_ctx* ctx, revive_stream stream, revive_graph** out) {
+  if (out) *out = nullptr;
+  if (!ctx || !out) return fail(ctx, REVIVE_EINVAL, "revive_graph_end: null argument");
+  hipGraph_t graph = nullptr;
+  REVIVE_HIP(ctx, hipStreamEndCapture(static_cast<hipStream_t>(stream), &graph));
+  hipGraphExec_t exec = nullptr;
+  int rc = check_hip(ctx, hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0), "hipGraphInstantiate");
+  if (rc != REVIVE_OK) {
+    (void)hipGraphDestroy(graph);
+    return rc;
+  }
+  revive_graph* g = new (std::nothrow) revive_graph();
+  if (!g) {
+    (void)hipGraphExecDestroy(exec);
+    (void)hipGraphDestroy(graph);
+    return fail(ctx, REVIVE_ENOMEM, "revive_graph_end: out of host memory");
+  }
+  g->graph = graph;
+  g->exec = exec;
+  *out = g;
+  return REVIVE_OK;
+}
+
+int revive_graph_launch(revive_graph* g, revive_stream stream) {
+  if (!g) return fail(nullptr, REVIVE_EINVAL, "revive_graph_launch: null graph");
+  return check_hip(nullptr, hipGraphLaunch(g->exec, static_cast<hipStream_t>(stream)), "hipGraphLaunch");
+}
+
+uintptr_t revive_graph_exec_id(const revive_graph* g) { return g ? reinterpret_cast<uintptr_t>(g->exec) : 0; }
+
+int revive_graph_destroy(revive_graph* g) {
+  if (!g) return REVIVE_OK;
+  (void)hipGraphExecDestroy(g->exec);
+  (void)hipGraphDestroy(g->graph);
+  delete g;
+  return REVIVE_OK;
+}
+
+// ---- timing ----
+
+int revive_set_kernel_timing(revive_ctx* ctx, int32_t enabled) {
+  if (!ctx) return fail(ctx, REVIVE_EINVAL, "revive_set_kernel_timing: null context");
+  if (enabled && ctx->slots.empty()) {
+    ctx->slots.resize(kTimingPairs);
+    for (auto& s : ctx->slots) {
+      REVIVE_HIP(ctx, hipEventCreate(&s.start));
+      REVIVE_HIP(ctx, hipEventCreate(&s.stop));
+    }
+  }
+  if (!enabled && ctx->timing) {
+    int rc = fold_timing(ctx);
+    if (rc != REVIVE_OK) return rc;
+  }
+  ctx->timing = enabled != 0;
+  return REVIVE_OK;
+}
+
+int revive_kernel_time(revive_ctx* ctx, int32_t kernel, double* total_ms, int64_t* launches) {
+  if (!ctx || kernel < 0 || kernel >= REVIVE_K_COUNT) return fail(ctx, REVIVE_EINVAL, "revive_kernel_time: bad argument");
+  int rc = fold_timing(ctx);
+  if (rc != REVIVE_OK) return rc;
+  if (total_ms) *total_ms = ctx->time_ms[kernel];
+  if (launches) *launches = ctx->time_n[kernel];
+  return REVIVE_OK;
+}
+
+int revive_reset_kernel_times(revive_ctx* ctx) {
+  if (!ctx) return fail(ctx, REVIVE_EINVAL, "revive_reset_kernel_times: null context");
+  int rc = fold_timing(ctx);
+  for (int i = 0; i < REVIVE_K_COUNT; ++i) {
+    ctx->time_ms[i] = 0;
+    ctx->time_n[i] = 0;
+  }
+  return rc;
+}
+
+const char* revive_kernel_name(int32_t kernel) {
+  static const char* names[REVIVE_K_COUNT] = {
+      "router_gemm", "route_topk", "dispatch_count", "dispatch_scan", "dispatch_place", "dispatch_permute",
+      "ffn_tiles", "ffn_gate_up", "ffn_down", "ffn_shared_gate_up", "ffn_shared_down", "combine"};
+  return kernel >= 0 && kernel < REVIVE_K_COUNT ? names[kernel] : "?";
+}
+
+const char* revive_last_error(const revive_ctx* ctx) { return ctx ? ctx->err.c_str() : g_noctx_error.c_str(); }
+
+const char* revive_status_name(int status) {
+  switch (status) {
+    case REVIVE_OK: return "REVIVE_OK";
+    case REVIVE_EINVAL: return "REVIVE_EINVAL";
+    case REVIVE_ENOMEM: return "REVIVE_ENOMEM";
+    case REVIVE_ESTATE: return "REVIVE_ESTATE";
+    case REVIVE_EINSUFFICIENT_EXPERTS: return "REVIVE_EINSUFFICIENT_EXPERTS";
+    case REVIVE_EHIP: return "REVIVE_EHIP";
+    default: return "REVIVE_?";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,141 @@
+// Internal context of the failure-remapped MoE layer library (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "revive.h"
+
+namespace revive {
+
+constexpr int kMaxE = 512;
+constexpr int kMaxP = 1024;
+constexpr int kMaxK = 32;
+constexpr int kDispatchChunk = 1024;  // routed rows handled by one block of the count/place kernels
+constexpr int kTimingPairs = 8192;    // event pairs kept before timing results are folded
+
+// Tile heights of the grouped GEMMs (rows of one slot handled by one workgroup).
+constexpr int kTileM_bf16 = 256;
+constexpr int kTileM_f32 = 64;
+
+// One row-tile of a grouped GEMM: rows [row_begin, row_end) all belong to `group`.
+struct MTile {
+  int32_t group;
+  int32_t row_begin;
+  int32_t row_end;
+  int32_t pad;
+};
+
+// Device-resident map, one contiguous blob at a fixed address so that one copy updates it.
+struct MapLayout {
+  size_t off_count;   // int32 [E]
+  size_t off_table;   // int32 [E * max_replicas]
+  size_t off_alive;   // uint8 [P] (padded to 4)
+  size_t bytes;
+};
+
+struct Workspace {
+  size_t off_block_hist;  // int32 [n_chunks_max * P]
+  size_t off_tiles;       // MTile [max_tiles_routed]
+  size_t off_tile_count;  // int32 [4]
+  size_t off_h;           // dtype [N_max * I]
+  size_t off_h_shared;    // dtype [T_max * I_shared]
+  size_t bytes;
+};
+
+struct TimingSlot {
+  hipEvent_t start, stop;
+  int kernel;
+};
+
+}  // namespace revive
+
+struct revive_ctx {
+  revive_config cfg;
+  int device = 0;
+  int P = 0;
+  size_t elem = 2;  // bytes per element of dtype
+
+  // host side of the map
+  std::vector<int32_t> phys_to_logical;
+  std::vector<int32_t> full_count;  // replicas per expert in the placement
+  std::vector<uint8_t> host_blob;   // current tables, MapLayout order
+  bool placement_set = false;
+  bool map_set = false;
+
+  // device side of the map (fixed addresses)
+  revive::MapLayout map{};
+  uint8_t* d_map = nullptr;
+  int32_t* d_phys_to_logical = nullptr;
+  // pinned staging, two buffers used alternately
+  uint8_t* h_stage[2] = {nullptr, nullptr};
+  hipEvent_t stage_done[2] = {nullptr, nullptr};
+  bool stage_used[2] = {false, false};
+  int stage_next = 0;
+
+  // caller-owned scratch
+  revive::Workspace ws{};
+  uint8_t* d_ws = nullptr;
+  size_t ws_bound = 0;
+
+  // timing
+  bool timing = false;
+  std::vector<revive::TimingSlot> slots;
+  size_t slots_used = 0;
+  double time_ms[REVIVE_K_COUNT] = {0};
+  int64_t time_n[REVIVE_K_COUNT] = {0};
+
+  mutable std::string err;
+
+  const int32_t* d_l2p_count() const { return reinterpret_cast<const int32_t*>(d_map + map.off_count); }
+  const int32_t* d_l2p_table() const { return reinterpret_cast<const int32_t*>(d_map + map.off_table); }
+  const uint8_t* d_slot_alive() const { return d_map + map.off_alive; }
+};
+
+namespace revive {
+
+int fail(const revive_ctx* ctx, int status, const char* fmt, ...);
+int check_hip(const revive_ctx* ctx, hipError_t e, const char* what);
+
+// Brackets one kernel launch with timing events when timing is on and the stream is not capturing.
+struct KernelTimer {
+  revive_ctx* ctx;
+  hipStream_t stream;
+  TimingSlot* slot = nullptr;
+  KernelTimer(revive_ctx* c, int kernel, hipStream_t s);
+  ~KernelTimer();
+};
+int fold_timing(revive_ctx* ctx);
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Upper bound on row-tiles of a grouped GEMM over N rows in at most `groups` non-empty groups.
+inline int max_tiles(int64_t n_rows, int groups, int tile_m) {
+  return static_cast<int>(n_rows / tile_m) + groups;
+}
+
+// Data-path stages, one translation unit each.
+int launch_router_gemm(revive_ctx*, const void* x, const void* w, float* logits, int T, hipStream_t);
+int launch_route_topk(revive_ctx*, const float* logits, int T, int32_t* topk_logical, float* topk_weight,
+                      int32_t* topk_phys, hipStream_t);
+int launch_dispatch(revive_ctx*, const void* x, const int32_t* topk_phys, int T, void* x_perm,
+                    int32_t* slot_offsets, int32_t* dst_row, int32_t* src_of, hipStream_t);
+int launch_expert_ffn(revive_ctx*, const void* x_perm, const int32_t* slot_offsets, const void* const* w_gate_up,
+                      const void* const* w_down, void* y_perm, const void* x, const void* w_sh_gate_up,
+                      const void* w_sh_down, void* y_shared, int T, hipStream_t);
+int launch_combine(revive_ctx*, const void* y_perm, const int32_t* dst_row, const float* topk_weight,
+                   const void* y_shared, int T, void* out, hipStream_t);
+
+}  // namespace revive
+
+#define REVIVE_HIP(ctx, call)                                           \
+  do {                                                                  \
+    int _rc = revive::check_hip((ctx), (call), #call);                  \
+    if (_rc != REVIVE_OK) return _rc;                                   \
+  } while (0)

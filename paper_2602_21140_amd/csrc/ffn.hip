@@ -1,0 +1,144 @@
+// Grouped SwiGLU expert FFN of the failure-remapped MoE layer.
+//
+// Paper: Sec. 2.1 (each expert acts as an FFN).  Every physical slot p that received rows
+// [slot_offsets[p], slot_offsets[p+1]) of the permuted activations applies its own weights:
+// h = silu(X G_p) * (X U_p), y = h D_p.  Slots without rows (in particular every slot of a failed
+// rank, Sec. 3.5) produce no tile, so their weight pointers are never dereferenced.
+//
+// The row counts exist only on the device, so the launch is shaped by an upper bound: a small
+// kernel turns slot_offsets into a list of row-tiles (slot, first row, end row) and the GEMM
+// grids cover floor(N / tile) + P tiles; workgroups beyond the list's end exit at once.
+#include "gemm_bf16.hpp"
+#include "gemm_f32.hpp"
+
+namespace revive {
+
+namespace {
+
+__global__ __launch_bounds__(kMaxP) void ffn_tiles_kernel(const int32_t* __restrict__ slot_offsets, int P, int tile_m,
+                                                          MTile* __restrict__ tiles, int32_t* __restrict__ tile_count) {
+  __shared__ int wave_sums[kMaxP / 64];
+  const int p = threadIdx.x;
+  int first = 0, end = 0;
+  if (p < P) {
+    first = slot_offsets[p];
+    end = slot_offsets[p + 1];
+  }
+  const int mine = end > first ? (end - first + tile_m - 1) / tile_m : 0;
+  const int lane = p & 63, wave = p >> 6;
+  int incl = mine;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int v = __shfl_up(incl, o);
+    if (lane >= o) incl += v;
+  }
+  if (lane == 63) wave_sums[wave] = incl;
+  __syncthreads();
+  if (wave == 0) {
+    const int w = lane < kMaxP / 64 ? wave_sums[lane] : 0;
+    int wi = w;
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) {
+      const int v = __shfl_up(wi, o);
+      if (lane >= o) wi += v;
+    }
+    if (lane < kMaxP / 64) wave_sums[lane] = wi - w;
+    if (lane == kMaxP / 64 - 1) tile_count[0] = wi;
+  }
+  __syncthreads();
+  const int base = wave_sums[wave] + incl - mine;
+  for (int i = 0; i < mine; ++i) {
+    MTile t;
+    t.group = p;
+    t.row_begin = first + i * tile_m;
+    t.row_end = min(end, first + (i + 1) * tile_m);
+    t.pad = 0;
+    tiles[base + i] = t;
+  }
+}
+
+// Tile shapes of the bf16 GEMMs: 256 x 256 x 64 per workgroup of 8 wavefronts (2 x 4).
+constexpr int kBM = kTileM_bf16, kBN = 256, kWM = 2, kWN = 4;
+
+int bf16_gemm_pair(revive_ctx* ctx, const void* A, const void* const* gu_tab, const void* gu_one, const void* const* dn_tab,
+                   const void* dn_one, void* h, void* y, int I, const MTile* tiles, const int32_t* tile_count, int M,
+                   int max_m_tiles, int k_gate_up, int k_down, hipStream_t stream) {
+  const int H = ctx->cfg.H;
+  GemmArgs a{};
+  a.A = A; a.lda = H;
+  a.B_tab = gu_tab; a.B_one = gu_one; a.ldb = H;
+  a.C = h; a.ldc = I;
+  a.n_out = I; a.K = H;
+  a.tiles = tiles; a.tile_count = tile_count; a.M = M;
+  a.n_col_tiles = ceil_div(I, kBN / 2);
+  {
+    KernelTimer timer(ctx, k_gate_up, stream);
+    int rc = launch_gemm_bf16<kBM, kBN, kWM, kWN, EPI_SWIGLU>(ctx, a, max_m_tiles, stream);
+    if (rc != REVIVE_OK) return rc;
+  }
+  GemmArgs d{};
+  d.A = h; d.lda = I;
+  d.B_tab = dn_tab; d.B_one = dn_one; d.ldb = I;
+  d.C = y; d.ldc = H;
+  d.n_out = H; d.K = I;
+  d.tiles = tiles; d.tile_count = tile_count; d.M = M;
+  d.n_col_tiles = ceil_div(H, kBN);
+  KernelTimer timer(ctx, k_down, stream);
+  return launch_gemm_bf16<kBM, kBN, kWM, kWN, EPI_BF16>(ctx, d, max_m_tiles, stream);
+}
+
+int f32_gemm_pair(revive_ctx* ctx, const void* A, const void* const* gu_tab, const void* gu_one, const void* const* dn_tab,
+                  const void* dn_one, void* h, void* y, int I, const MTile* tiles, const int32_t* tile_count, int M,
+                  int max_m_tiles, int k_gate_up, int k_down, hipStream_t stream) {
+  const int H = ctx->cfg.H;
+  GemmF32Args a{};
+  a.A = static_cast<const float*>(A); a.lda = H;
+  a.B_tab = gu_tab; a.B_one = static_cast<const float*>(gu_one); a.ldb = H;
+  a.C = static_cast<float*>(h); a.ldc = I;
+  a.n_out = I; a.K = H;
+  a.tiles = tiles; a.tile_count = tile_count; a.M = M;
+  a.n_col_tiles = ceil_div(I, 64);
+  {
+    KernelTimer timer(ctx, k_gate_up, stream);
+    int rc = launch_gemm_f32<true>(ctx, a, max_m_tiles, stream);
+    if (rc != REVIVE_OK) return rc;
+  }
+  GemmF32Args d{};
+  d.A = static_cast<const float*>(h); d.lda = I;
+  d.B_tab = dn_tab; d.B_one = static_cast<const float*>(dn_one); d.ldb = I;
+  d.C = static_cast<float*>(y); d.ldc = H;
+  d.n_out = H; d.K = I;
+  d.tiles = tiles; d.tile_count = tile_count; d.M = M;
+  d.n_col_tiles = ceil_div(H, 64);
+  KernelTimer timer(ctx, k_down, stream);
+  return launch_gemm_f32<false>(ctx, d, max_m_tiles, stream);
+}
+
+}  // namespace
+
+int launch_expert_ffn(revive_ctx* ctx, const void* x_perm, const int32_t* slot_offsets, const void* const* w_gate_up,
+                      const void* const* w_down, void* y_perm, const void* x, const void* w_sh_gate_up, const void* w_sh_down,
+                      void* y_shared, int T, hipStream_t stream) {
+  const revive_config& c = ctx->cfg;
+  const bool bf16 = c.dtype == REVIVE_DTYPE_BF16;
+  const int tile_m = bf16 ? kTileM_bf16 : kTileM_f32;
+  const int64_t N = static_cast<int64_t>(T) * c.k;
+  MTile* tiles = reinterpret_cast<MTile*>(ctx->d_ws + ctx->ws.off_tiles);
+  int32_t* tile_count = reinterpret_cast<int32_t*>(ctx->d_ws + ctx->ws.off_tile_count);
+  void* h = ctx->d_ws + ctx->ws.off_h;
+  void* h_shared = ctx->d_ws + ctx->ws.off_h_shared;
+  {
+    KernelTimer timer(ctx, REVIVE_K_FFN_TILES, stream);
+    hipLaunchKernelGGL(ffn_tiles_kernel, dim3(1), dim3(kMaxP), 0, stream, slot_offsets, ctx->P, tile_m, tiles, tile_count);
+    REVIVE_HIP(ctx, hipGetLastError());
+  }
+  const int bound = max_tiles(N, ctx->P, tile_m);
+  auto pair = bf16 ? bf16_gemm_pair : f32_gemm_pair;
+  int rc = pair(ctx, x_perm, w_gate_up, nullptr, w_down, nullptr, h, y_perm, c.I, tiles, tile_count, 0, bound,
+                REVIVE_K_FFN_GATE_UP, REVIVE_K_FFN_DOWN, stream);
+  if (rc != REVIVE_OK || !y_shared) return rc;
+  return pair(ctx, x, nullptr, w_sh_gate_up, nullptr, w_sh_down, h_shared, y_shared, c.I_shared, nullptr, nullptr, T,
+              ceil_div(T, tile_m), REVIVE_K_FFN_SHARED_GATE_UP, REVIVE_K_FFN_SHARED_DOWN, stream);
+}
+
+}  // namespace revive

@@ -1,0 +1,266 @@
+// Grouped bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulate.
+//
+//   C[rows of tile, n] = sum_k A[row, k] * B_group[n, k]        ("NT": both operands K-contiguous)
+//
+// A is one tall activation matrix whose rows are split into row-tiles that each belong to one
+// group (physical expert slot); B is that group's output-major weight matrix.  Three epilogues:
+//   EPI_F32     store fp32                         (router logits)
+//   EPI_BF16    round to bf16 and store            (down projection)
+//   EPI_SWIGLU  B holds gate rows [0, n_out) and up rows [n_out, 2 n_out); store
+//               bf16(silu(gate) * up)              (gate/up projection of a SwiGLU expert)
+//
+// Work decomposition: one workgroup computes a BM x BN tile with WAVES_M x WAVES_N wavefronts of
+// 64 lanes; each wavefront owns (BM/WAVES_M) x (BN/WAVES_N) outputs as 32x32 MFMA tiles.  K is
+// walked in steps of 64: the next step's global loads are issued into registers before the MFMAs
+// of the current step and written to the other half of a double-buffered LDS tile afterwards, one
+// barrier per step.  LDS rows are 128 bytes (64 bf16); the 16-byte chunk index is XOR-ed with
+// (row & 7) so that both the 16-byte writes and the per-lane 16-byte fragment reads are
+// conflict-free.  The weights go in as the MFMA's first operand so that each lane ends up with
+// four consecutive output columns of one activation row, which it stores as one 8/16-byte word.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "ctx.hpp"
+
+namespace revive {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+enum { EPI_F32 = 0, EPI_BF16 = 1, EPI_SWIGLU = 2 };
+
+struct GemmArgs {
+  const void* A;             // [rows, K] bf16
+  int64_t lda;               // elements between rows of A
+  const void* const* B_tab;  // device table: group -> [n_rows_B, K] bf16, or null
+  const void* B_one;         // used for every group when B_tab is null
+  int64_t ldb;               // elements between rows of B
+  void* C;                   // [rows, n_out] fp32 or bf16
+  int64_t ldc;
+  int n_out;                 // output columns (SwiGLU: I, with B holding 2*I rows)
+  int K;                     // multiple of 64
+  const MTile* tiles;        // device row-tile list, or null for a dense [0, M) matrix
+  const int32_t* tile_count; // device count of valid entries in `tiles`
+  int M;                     // dense case: number of rows
+  int n_col_tiles;
+};
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// Round-to-nearest-even fp32 -> bf16 bits (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+__device__ __forceinline__ float silu_f32(float z) { return z / (1.0f + __expf(-z)); }
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmArgs g) {
+  constexpr int NT = 64 * WAVES_M * WAVES_N;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int ITER_A = BM * 8 / NT, ITER_B = BN * 8 / NT;
+  constexpr int BN_OUT = EPI == EPI_SWIGLU ? BN / 2 : BN;  // output columns per workgroup
+  constexpr int STAGE = (BM + BN) * 128;                   // bytes of one LDS stage
+  static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "tile shape");
+  static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0, "load split");
+  static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU needs gate and up tiles in one wave");
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+  // ---- which tile is mine: spread the valid tiles evenly over the 8 XCDs (workgroup i runs on
+  // XCD i % 8) so that each XCD's L2 sees a contiguous run of tiles sharing activations/weights.
+  const int n_m_tiles = g.tiles ? *g.tile_count : (g.M + BM - 1) / BM;
+  const int total = n_m_tiles * g.n_col_tiles;
+  const int per_xcd = (total + 7) >> 3;
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int logical = xcd * per_xcd + local;
+  if (local >= per_xcd || logical >= total) return;
+  const int m_idx = logical / g.n_col_tiles;
+  const int n_idx = logical - m_idx * g.n_col_tiles;
+
+  int group = 0, row_begin, row_end;
+  if (g.tiles) {
+    const MTile t = g.tiles[m_idx];
+    group = t.group;
+    row_begin = t.row_begin;
+    row_end = t.row_end;
+  } else {
+    row_begin = m_idx * BM;
+    row_end = min(g.M, row_begin + BM);
+  }
+  const unsigned char* Bbase = static_cast<const unsigned char*>(g.B_tab ? g.B_tab[group] : g.B_one);
+  const unsigned char* Abase = static_cast<const unsigned char*>(g.A);
+  const int n0 = n_idx * BN_OUT;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+  // ---- per-thread global sources and LDS destinations of the cooperative tile loads
+  const unsigned char* a_src[ITER_A];
+  const unsigned char* b_src[ITER_B];
+  int a_dst[ITER_A], b_dst[ITER_B];
+#pragma unroll
+  for (int it = 0; it < ITER_A; ++it) {
+    const int idx = it * NT + tid, row = idx >> 3, chunk = idx & 7;
+    const int grow = min(row_begin + row, row_end - 1);  // rows past the tile re-read its last row
+    a_src[it] = Abase + (static_cast<int64_t>(grow) * g.lda + chunk * 8) * 2;
+    a_dst[it] = row * 128 + ((chunk ^ (row & 7)) << 4);
+  }
+#pragma unroll
+  for (int it = 0; it < ITER_B; ++it) {
+    const int idx = it * NT + tid, row = idx >> 3, chunk = idx & 7;
+    int brow;
+    if (EPI == EPI_SWIGLU) {
+      const int half = row >= BN / 2;
+      const int col = min(n0 + row - half * (BN / 2), g.n_out - 1);
+      brow = col + half * g.n_out;
+    } else {
+      brow = min(n0 + row, g.n_out - 1);
+    }
+    b_src[it] = Bbase + (static_cast<int64_t>(brow) * g.ldb + chunk * 8) * 2;
+    b_dst[it] = BM * 128 + row * 128 + ((chunk ^ (row & 7)) << 4);
+  }
+
+  // ---- per-lane LDS fragment addresses (without the k-step part)
+  int a_frag[TM], b_frag[TN];
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm) a_frag[tm] = wm * WM + tm * 32 + (lane & 31);
+#pragma unroll
+  for (int tn = 0; tn < TN; ++tn) {
+    int r;
+    if (EPI == EPI_SWIGLU) {
+      const int half = tn >= TN / 2;
+      r = half * (BN / 2) + wn * (WN / 2) + (tn - half * (TN / 2)) * 32 + (lane & 31);
+    } else {
+      r = wn * WN + tn * 32 + (lane & 31);
+    }
+    b_frag[tn] = BM + r;
+  }
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0.f;
+
+  u32x4 a_reg[ITER_A], b_reg[ITER_B];
+  auto load_global = [&](int kt) {
+    const int64_t koff = static_cast<int64_t>(kt) * 128;  // 64 bf16
+#pragma unroll
+    for (int it = 0; it < ITER_A; ++it) a_reg[it] = *reinterpret_cast<const u32x4*>(a_src[it] + koff);
+#pragma unroll
+    for (int it = 0; it < ITER_B; ++it) b_reg[it] = *reinterpret_cast<const u32x4*>(b_src[it] + koff);
+  };
+  auto store_lds = [&](int stage) {
+    unsigned char* base = smem + stage * STAGE;
+#pragma unroll
+    for (int it = 0; it < ITER_A; ++it) *reinterpret_cast<u32x4*>(base + a_dst[it]) = a_reg[it];
+#pragma unroll
+    for (int it = 0; it < ITER_B; ++it) *reinterpret_cast<u32x4*>(base + b_dst[it]) = b_reg[it];
+  };
+
+  const int KT = g.K >> 6;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+
+  for (int kt = 0; kt < KT; ++kt) {
+    if (kt + 1 < KT) load_global(kt + 1);
+    const unsigned char* base = smem + (kt & 1) * STAGE;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int chunk = ks * 2 + (lane >> 5);
+      bf16x8 af[TM], bfr[TN];
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm) {
+        const int r = a_frag[tm];
+        af[tm] = *reinterpret_cast<const bf16x8*>(base + r * 128 + ((chunk ^ (r & 7)) << 4));
+      }
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) {
+        const int r = b_frag[tn];
+        bfr[tn] = *reinterpret_cast<const bf16x8*>(base + r * 128 + ((chunk ^ (r & 7)) << 4));
+      }
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+          acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tn], af[tm], acc[tm][tn], 0, 0, 0);
+    }
+    if (kt + 1 < KT) store_lds((kt + 1) & 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue.  Lane holds, per 32x32 tile, for q = 0..3 the four columns
+  // q*8 + (lane/32)*4 + {0..3} of activation row lane % 32.
+  constexpr int TN_OUT = EPI == EPI_SWIGLU ? TN / 2 : TN;
+  constexpr int WN_OUT = EPI == EPI_SWIGLU ? WN / 2 : WN;
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm) {
+    const int row = row_begin + wm * WM + tm * 32 + (lane & 31);
+    if (row >= row_end) continue;
+#pragma unroll
+    for (int tn = 0; tn < TN_OUT; ++tn) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = n0 + wn * WN_OUT + tn * 32 + q * 8 + (lane >> 5) * 4;
+        if (col >= g.n_out) continue;
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          if (EPI == EPI_SWIGLU) v[r] = silu_f32(acc[tm][tn][q * 4 + r]) * acc[tm][tn + TN / 2][q * 4 + r];
+          else v[r] = acc[tm][tn][q * 4 + r];
+        }
+        const int64_t off = static_cast<int64_t>(row) * g.ldc + col;
+        if (col + 3 < g.n_out && (g.ldc & 3) == 0) {
+          if (EPI == EPI_F32) {
+            f32x4 o = {v[0], v[1], v[2], v[3]};
+            *reinterpret_cast<f32x4*>(static_cast<float*>(g.C) + off) = o;
+          } else {
+            u32x2 o = {f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16),
+                       f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16)};
+            *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(g.C) + off) = o;
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            if (col + r >= g.n_out) break;
+            if (EPI == EPI_F32) static_cast<float*>(g.C)[off + r] = v[r];
+            else static_cast<uint16_t*>(g.C)[off + r] = static_cast<uint16_t>(f32_to_bf16_bits(v[r]));
+          }
+        }
+      }
+    }
+  }
+}
+
+// Launch helper: grid covers `max_m_tiles` row-tiles (an upper bound; surplus workgroups exit).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
+int launch_gemm_bf16(revive_ctx* ctx, const GemmArgs& args, int max_m_tiles, hipStream_t stream) {
+  constexpr int NT = 64 * WAVES_M * WAVES_N;
+  constexpr size_t lds = 2 * (BM + BN) * 128;
+  auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, EPI>;
+  static bool configured = false;  // per instantiation
+  if (!configured) {
+    REVIVE_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        static_cast<int>(lds)));
+    configured = true;
+  }
+  const int64_t total = static_cast<int64_t>(max_m_tiles) * args.n_col_tiles;
+  if (total <= 0) return REVIVE_OK;
+  const int grid = static_cast<int>((total + 7) / 8 * 8);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, stream, args);
+  return check_hip(ctx, hipGetLastError(), "gemm_bf16 launch");
+}
+
+}  // namespace revive

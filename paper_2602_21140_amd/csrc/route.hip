@@ -1,0 +1,191 @@
+// Gate of the failure-remapped MoE layer: router logits, failure-masked (group-limited) top-k,
+// renormalised weights and the logical->physical replica remap.
+//
+// Paper: Sec. 2.1 (gating scores, top-k), Sec. 3.4 "Missing experts" and Sec. 4.2 (experts with
+// no replica left are masked to -inf immediately before the top-k), Sec. 3.4 "Redundant experts"
+// (the logical-to-physical map decides which replica serves a token).
+#include "gemm_bf16.hpp"
+#include "gemm_f32.hpp"
+
+namespace revive {
+
+namespace {
+
+constexpr int kVals = kMaxE / 64;  // logits held per lane
+
+// Ordering of candidates: larger key first, equal keys by lower expert id.
+__device__ __forceinline__ bool better(float ka, int ea, float kb, int eb) { return ka > kb || (ka == kb && ea < eb); }
+
+struct RouteParams {
+  const float* logits;
+  const int32_t* l2p_count;
+  const int32_t* l2p_table;
+  int32_t* topk_logical;
+  float* topk_weight;
+  int32_t* topk_phys;
+  int T, E, k, max_replicas, score_fn, n_group, topk_group;
+  float route_scale;
+};
+
+// One wavefront per token.  Lane l holds the logits of experts l, l+64, l+128, ...; a masked or
+// excluded expert's key is -inf.  Expert order is decided on the fp32 logits themselves (softmax
+// and sigmoid are increasing, so this is the order of the scores); group scores, which add two
+// scores, and the output weights are evaluated in fp64.
+__global__ __launch_bounds__(256) void route_topk_kernel(RouteParams p) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= p.T) return;  // whole wavefront leaves together
+  const float NEG = -__builtin_inff();
+
+  float key[kVals];
+  const float* row = p.logits + static_cast<int64_t>(t) * p.E;
+  float vmax = NEG;  // largest logit of the row, masked or not: common shift of the exponentials
+#pragma unroll
+  for (int i = 0; i < kVals; ++i) {
+    const int e = lane + 64 * i;
+    float z = NEG;
+    if (e < p.E) {
+      z = row[e];
+      vmax = fmaxf(vmax, z);
+      if (p.l2p_count[e] <= 0) z = NEG;  // failure mask
+    }
+    key[i] = z;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) vmax = fmaxf(vmax, __shfl_xor(vmax, o));
+  const double shift = static_cast<double>(vmax);
+
+  auto score64 = [&](float z) -> double {  // unnormalised gating score of a live expert
+    const double zd = static_cast<double>(z);
+    return p.score_fn == REVIVE_SCORE_SIGMOID ? 1.0 / (1.0 + exp(-zd)) : exp(zd - shift);
+  };
+
+  if (p.n_group > 1) {
+    // Group score = sum of the two best live scores of the group (one if only one is live, -inf
+    // if none).  Computed by every lane redundantly after a wave-wide top-2 per group.
+    const int gsz = p.E / p.n_group;
+    double gscore[32];
+#pragma unroll 1
+    for (int g = 0; g < p.n_group; ++g) {
+      float m1 = NEG, m2 = NEG;  // the lane's two best keys inside group g
+#pragma unroll
+      for (int i = 0; i < kVals; ++i) {
+        const int e = lane + 64 * i;
+        const float z = (e < p.E && e / gsz == g) ? key[i] : NEG;
+        if (z > m1) { m2 = m1; m1 = z; } else if (z > m2) { m2 = z; }
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        const float o1 = __shfl_xor(m1, o), o2 = __shfl_xor(m2, o);
+        const float hi = fmaxf(m1, o1);
+        const float lo = fmaxf(fminf(m1, o1), fmaxf(m2, o2));
+        m1 = hi;
+        m2 = lo;
+      }
+      double s = -__builtin_inf();
+      if (m1 > NEG) {
+        s = score64(m1);
+        if (m2 > NEG) s += score64(m2);
+      }
+      gscore[g] = s;
+    }
+    // Keep the topk_group best groups, ties to the lower group id; drop the experts of the rest.
+#pragma unroll 1
+    for (int g = 0; g < p.n_group; ++g) {
+      int rank = 0;
+      for (int h = 0; h < p.n_group; ++h) rank += (gscore[h] > gscore[g]) || (gscore[h] == gscore[g] && h < g);
+      if (rank >= p.topk_group) {
+#pragma unroll
+        for (int i = 0; i < kVals; ++i) {
+          const int e = lane + 64 * i;
+          if (e < p.E && e / gsz == g) key[i] = NEG;
+        }
+      }
+    }
+  }
+
+  // k rounds of wave-wide arg-max; the winner of round j lands in lane j.
+  int my_e = -1;
+  float my_z = 0.f;
+  for (int j = 0; j < p.k; ++j) {
+    float bk = NEG;
+    int be = 0x7fffffff;
+#pragma unroll
+    for (int i = 0; i < kVals; ++i) {
+      const int e = lane + 64 * i;
+      if (e < p.E && better(key[i], e, bk, be)) { bk = key[i]; be = e; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float ok = __shfl_xor(bk, o);
+      const int oe = __shfl_xor(be, o);
+      if (better(ok, oe, bk, be)) { bk = ok; be = oe; }
+    }
+    if ((be & 63) == lane) {
+#pragma unroll
+      for (int i = 0; i < kVals; ++i)
+        if (i == (be >> 6)) key[i] = NEG;
+    }
+    if (lane == j) { my_e = be; my_z = bk; }
+  }
+
+  // weights: score of the chosen expert over the sum of the chosen scores
+  double s = (lane < p.k) ? score64(my_z) : 0.0;
+  double sum = s;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+  if (lane < p.k) {
+    const int64_t o = static_cast<int64_t>(t) * p.k + lane;
+    const int c = p.l2p_count[my_e];
+    p.topk_logical[o] = my_e;
+    p.topk_weight[o] = static_cast<float>(s / sum * static_cast<double>(p.route_scale));
+    // replica of this token: the (t mod count)-th surviving slot, ascending slot id
+    p.topk_phys[o] = c > 0 ? p.l2p_table[my_e * p.max_replicas + t % c] : -1;
+  }
+}
+
+}  // namespace
+
+int launch_router_gemm(revive_ctx* ctx, const void* x, const void* w, float* logits, int T, hipStream_t stream) {
+  const revive_config& c = ctx->cfg;
+  KernelTimer timer(ctx, REVIVE_K_ROUTER_GEMM, stream);
+  if (c.dtype == REVIVE_DTYPE_BF16) {
+    GemmArgs a{};
+    a.A = x; a.lda = c.H;
+    a.B_tab = nullptr; a.B_one = w; a.ldb = c.H;
+    a.C = logits; a.ldc = c.E;
+    a.n_out = c.E; a.K = c.H;
+    a.tiles = nullptr; a.tile_count = nullptr; a.M = T;
+    constexpr int BM = 128, BN = 64;
+    a.n_col_tiles = ceil_div(c.E, BN);
+    return launch_gemm_bf16<BM, BN, 4, 1, EPI_F32>(ctx, a, ceil_div(T, BM), stream);
+  }
+  GemmF32Args a{};
+  a.A = static_cast<const float*>(x); a.lda = c.H;
+  a.B_tab = nullptr; a.B_one = static_cast<const float*>(w); a.ldb = c.H;
+  a.C = logits; a.ldc = c.E;
+  a.n_out = c.E; a.K = c.H;
+  a.tiles = nullptr; a.tile_count = nullptr; a.M = T;
+  a.n_col_tiles = ceil_div(c.E, 64);
+  return launch_gemm_f32<false>(ctx, a, ceil_div(T, kTileM_f32), stream);
+}
+
+int launch_route_topk(revive_ctx* ctx, const float* logits, int T, int32_t* topk_logical, float* topk_weight,
+                      int32_t* topk_phys, hipStream_t stream) {
+  const revive_config& c = ctx->cfg;
+  RouteParams p{};
+  p.logits = logits;
+  p.l2p_count = ctx->d_l2p_count();
+  p.l2p_table = ctx->d_l2p_table();
+  p.topk_logical = topk_logical;
+  p.topk_weight = topk_weight;
+  p.topk_phys = topk_phys;
+  p.T = T; p.E = c.E; p.k = c.k; p.max_replicas = c.max_replicas;
+  p.score_fn = c.score_fn; p.n_group = c.n_group; p.topk_group = c.topk_group;
+  p.route_scale = c.route_scale;
+  KernelTimer timer(ctx, REVIVE_K_ROUTE_TOPK, stream);
+  hipLaunchKernelGGL(route_topk_kernel, dim3(ceil_div(T, 4)), dim3(256), 0, stream, p);
+  return check_hip(ctx, hipGetLastError(), "route_topk launch");
+}
+
+}  // namespace revive

@@ -1,0 +1,98 @@
+"""A layer resident in HBM: seeded inputs, per-slot packed weights, preallocated outputs.
+
+Plumbing around the binding for the tests, the smoke check and the benchmark: it draws the
+synthetic workload on the device, packs the weights into the library's layouts, owns every
+buffer the four data-path calls write, and can record those calls into one graph.  All compute
+happens inside the library calls.
+"""
+from __future__ import annotations
+
+from typing import Dict, Iterable, List, Optional
+
+import numpy as np
+import torch
+
+import synth
+
+from .binding import ReviveLayer, pack_expert, pack_router
+
+
+class ResidentLayer:
+    def __init__(self, cfg: synth.LayerConfig, device="cuda:0", with_weights=True, failed: Optional[Iterable[int]] = None,
+                 replica_copies=True):
+        self.cfg = cfg
+        self.device = device
+        self.layer = ReviveLayer(cfg, device=device)
+        self.p2l = synth.make_placement(cfg)
+        self.layer.set_placement(self.p2l)
+        self.failed = synth.failed_mask(cfg, failed)
+        self.stats = self.layer.update_map(self.failed)
+        self.x = synth.draw_x(cfg, device)
+        self.w_router = synth.draw_router(cfg, device)        # [H, E]
+        self.w_router_packed = pack_router(self.w_router)     # [E, H]
+        self.sh_gate_up = self.sh_down = None
+        self.gu: List[Optional[torch.Tensor]] = [None] * cfg.P
+        self.dn: List[Optional[torch.Tensor]] = [None] * cfg.P
+        if with_weights:
+            for e in range(cfg.E):
+                slots = np.nonzero(self.p2l == e)[0]
+                if slots.size == 0:
+                    continue
+                w = synth.draw_expert(cfg, e, device)
+                g, d = pack_expert(w["gate"], w["up"], w["down"])
+                del w
+                for i, p in enumerate(slots):   # each replica owns its own copy of the bits
+                    self.gu[p] = g if (i == 0 or not replica_copies) else g.clone()
+                    self.dn[p] = d if (i == 0 or not replica_copies) else d.clone()
+            self.layer.set_expert_weights(self.gu, self.dn)
+            sh = synth.draw_shared(cfg, device)
+            if sh is not None:
+                self.sh_gate_up, self.sh_down = pack_expert(sh["gate"], sh["up"], sh["down"])
+        T, k, H, E, P = cfg.T, cfg.k, cfg.H, cfg.E, cfg.P
+        L = self.layer
+        i32, f32 = torch.int32, torch.float32
+        self.buf: Dict[str, Optional[torch.Tensor]] = dict(
+            logits=L.empty(T, E, dtype=f32), topk_logical=L.empty(T, k, dtype=i32),
+            topk_weight=L.empty(T, k, dtype=f32), topk_phys=L.empty(T, k, dtype=i32),
+            x_perm=L.empty(T * k, H), slot_offsets=L.empty(P + 1, dtype=i32), dst_row=L.empty(T * k, dtype=i32),
+            src_of=L.empty(T * k, dtype=i32), y_perm=L.empty(T * k, H),
+            y_shared=L.empty(T, H) if self.sh_gate_up is not None else None, out=L.empty(T, H))
+        self.graph = None
+
+    def set_failed(self, failed: Iterable[int], stream=None) -> Dict[str, int]:
+        self.failed = synth.failed_mask(self.cfg, failed)
+        self.stats = self.layer.update_map(self.failed, stream=stream)
+        return self.stats
+
+    def forward(self, logits: Optional[torch.Tensor] = None, shared=True, stream=None) -> Dict[str, Optional[torch.Tensor]]:
+        """route -> dispatch -> expert_ffn -> combine into the preallocated buffers (returned)."""
+        c, L, b = self.cfg, self.layer, self.buf
+        T = c.T
+        out3 = (b["topk_logical"], b["topk_weight"], b["topk_phys"])
+        if logits is None:
+            L.route(self.x, self.w_router_packed, T, logits=b["logits"], out=out3, stream=stream)
+        else:
+            b["logits"].copy_(logits)
+            L.route(None, None, T, logits=b["logits"], logits_given=True, out=out3, stream=stream)
+        L.dispatch(self.x, b["topk_phys"], T, out=(b["x_perm"], b["slot_offsets"], b["dst_row"], b["src_of"]), stream=stream)
+        use_shared = shared and self.sh_gate_up is not None
+        L.expert_ffn(b["x_perm"], b["slot_offsets"], T, x=self.x, w_sh_gate_up=self.sh_gate_up, w_sh_down=self.sh_down,
+                     out=(b["y_perm"], b["y_shared"] if use_shared else None), shared=use_shared, stream=stream)
+        L.combine(b["y_perm"], b["dst_row"], b["topk_weight"], b["y_shared"] if use_shared else None, T, out=b["out"],
+                  stream=stream)
+        return b
+
+    def capture(self, stream: torch.cuda.Stream):
+        """Record one forward on `stream` into a graph (instantiated once)."""
+        self.layer.graph_begin(stream)
+        try:
+            self.forward(stream=stream)
+        finally:
+            self.graph = self.layer.graph_end(stream)
+        return self.graph
+
+    def replay(self, stream: torch.cuda.Stream):
+        self.layer.graph_launch(self.graph, stream)
+
+    def close(self):
+        self.layer.close()

@@ -1,0 +1,93 @@
+"""CPU checks of the C-ABI library: it loads, exports every declared symbol, and its host-side
+map construction agrees bit for bit with the oracle.  No GPU call is made."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import synth
+from oracle import revive_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _pk():
+    import paper_2602_21140_amd as pk
+    if not os.path.exists(pk.lib_path()):
+        from paper_2602_21140_amd import build
+        build.build(verbose=False)
+    return pk
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "revive.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(revive_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    pk = _pk()
+    L = pk.lib()
+    names = _declared()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in revive.h but not exported"
+    from paper_2602_21140_amd import binding
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_status_and_kernel_names():
+    L = _pk().lib()
+    assert L.revive_status_name(0) == b"REVIVE_OK" and L.revive_status_name(-4) == b"REVIVE_EINSUFFICIENT_EXPERTS"
+    from paper_2602_21140_amd import binding
+    for i, n in enumerate(binding.KERNEL_NAMES):
+        assert L.revive_kernel_name(i).decode() == n
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
+def test_host_map_build_matches_oracle(name):
+    pk = _pk()
+    cfg = synth.get_config(name)
+    p2l = synth.make_placement(cfg)
+    rng = np.random.default_rng(5)
+    cases = [synth.failed_mask(cfg), synth.failed_mask(cfg, [])]
+    for _ in range(4):
+        cases.append(synth.failed_mask(cfg, rng.choice(cfg.n_ranks, size=rng.integers(1, 3), replace=False)))
+    for failed in cases:
+        rc, table, count, alive, stats = pk.build_map_host(cfg, p2l, failed)
+        m = orc.build_map(p2l, failed, cfg.slots_per_rank, cfg.E, cfg.max_replicas)
+        ok = orc.enough_live_experts(m.l2p_count, cfg.k, cfg.n_group, cfg.topk_group)
+        assert (rc == 0) == ok
+        assert np.array_equal(table, m.l2p_table) and np.array_equal(count, m.l2p_count)
+        assert np.array_equal(alive, m.slot_alive)
+        assert stats == dict(n_live_slots=m.n_live_slots, n_live_experts=m.n_live_experts,
+                             n_lost_experts=m.n_lost_experts, n_degraded_experts=m.n_degraded_experts)
+
+
+def test_host_map_build_rejects_bad_input():
+    pk = _pk()
+    cfg = synth.get_config("c1")
+    p2l = synth.make_placement(cfg)
+    bad = synth.failed_mask(cfg)
+    bad[0] = 2
+    assert pk.build_map_host(cfg, p2l, bad)[0] == -1                      # byte not 0/1
+    assert pk.build_map_host(cfg, p2l, np.ones(cfg.n_ranks, np.uint8))[0] == -4   # nothing left alive
+    p2 = p2l.copy()
+    p2[3] = cfg.E
+    assert pk.build_map_host(cfg, p2, synth.failed_mask(cfg))[0] == -1    # expert id out of range
+    p3 = p2l.copy()
+    p3[:3] = 0
+    assert pk.build_map_host(cfg, p3, synth.failed_mask(cfg))[0] == -1    # more copies than max_replicas
+    # grouped sufficiency: 4 groups of 4, keep 2, k = 4; leave two groups with one live expert each
+    g = synth.scaled(cfg, n_group=4, topk_group=2, k=4, score_fn="sigmoid", slots_per_rank=1, max_replicas=1,
+                     n_ranks=16)
+    pg = np.arange(16, dtype=np.int32)
+    failed = np.zeros(16, np.uint8)
+    failed[[1, 2, 3, 5, 6, 7]] = 1
+    assert pk.build_map_host(g, pg, failed)[0] == -4
+    failed[5] = 0
+    assert pk.build_map_host(g, pg, failed)[0] == -4     # 1 + 2 < 4
+    failed[[1, 2]] = 0
+    assert pk.build_map_host(g, pg, failed)[0] == 0      # groups hold 3, 2, 4, 4: worst pair 2 + 3 >= 4
