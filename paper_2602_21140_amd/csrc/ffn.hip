@@ -60,9 +60,10 @@ __global__ __launch_bounds__(kMaxP) void ffn_tiles_kernel(const int32_t* __restr
 // Tile shapes of the bf16 GEMMs: 256 x 256 x 64 per workgroup of 8 wavefronts (2 x 4).
 constexpr int kBM = kTileM_bf16, kBN = 256, kWM = 2, kWN = 4;
 
+template <int K_GATE_UP, int K_DOWN>
 int bf16_gemm_pair(revive_ctx* ctx, const void* A, const void* const* gu_tab, const void* gu_one, const void* const* dn_tab,
                    const void* dn_one, void* h, void* y, int I, const MTile* tiles, const int32_t* tile_count, int M,
-                   int max_m_tiles, int k_gate_up, int k_down, hipStream_t stream) {
+                   int max_m_tiles, hipStream_t stream) {
   const int H = ctx->cfg.H;
   GemmArgs a{};
   a.A = A; a.lda = H;
@@ -72,8 +73,8 @@ int bf16_gemm_pair(revive_ctx* ctx, const void* A, const void* const* gu_tab, co
   a.tiles = tiles; a.tile_count = tile_count; a.M = M;
   a.n_col_tiles = ceil_div(I, kBN / 2);
   {
-    KernelTimer timer(ctx, k_gate_up, stream);
-    int rc = launch_gemm_bf16<kBM, kBN, kWM, kWN, EPI_SWIGLU>(ctx, a, max_m_tiles, stream);
+    KernelTimer timer(ctx, K_GATE_UP, stream);
+    int rc = launch_gemm_bf16<kBM, kBN, kWM, kWN, EPI_SWIGLU, K_GATE_UP>(ctx, a, max_m_tiles, stream);
     if (rc != REVIVE_OK) return rc;
   }
   GemmArgs d{};
@@ -83,13 +84,14 @@ int bf16_gemm_pair(revive_ctx* ctx, const void* A, const void* const* gu_tab, co
   d.n_out = H; d.K = I;
   d.tiles = tiles; d.tile_count = tile_count; d.M = M;
   d.n_col_tiles = ceil_div(H, kBN);
-  KernelTimer timer(ctx, k_down, stream);
-  return launch_gemm_bf16<kBM, kBN, kWM, kWN, EPI_BF16>(ctx, d, max_m_tiles, stream);
+  KernelTimer timer(ctx, K_DOWN, stream);
+  return launch_gemm_bf16<kBM, kBN, kWM, kWN, EPI_BF16, K_DOWN>(ctx, d, max_m_tiles, stream);
 }
 
+template <int K_GATE_UP, int K_DOWN>
 int f32_gemm_pair(revive_ctx* ctx, const void* A, const void* const* gu_tab, const void* gu_one, const void* const* dn_tab,
                   const void* dn_one, void* h, void* y, int I, const MTile* tiles, const int32_t* tile_count, int M,
-                  int max_m_tiles, int k_gate_up, int k_down, hipStream_t stream) {
+                  int max_m_tiles, hipStream_t stream) {
   const int H = ctx->cfg.H;
   GemmF32Args a{};
   a.A = static_cast<const float*>(A); a.lda = H;
@@ -99,7 +101,7 @@ int f32_gemm_pair(revive_ctx* ctx, const void* A, const void* const* gu_tab, con
   a.tiles = tiles; a.tile_count = tile_count; a.M = M;
   a.n_col_tiles = ceil_div(I, 64);
   {
-    KernelTimer timer(ctx, k_gate_up, stream);
+    KernelTimer timer(ctx, K_GATE_UP, stream);
     int rc = launch_gemm_f32<true>(ctx, a, max_m_tiles, stream);
     if (rc != REVIVE_OK) return rc;
   }
@@ -110,7 +112,7 @@ int f32_gemm_pair(revive_ctx* ctx, const void* A, const void* const* gu_tab, con
   d.n_out = H; d.K = I;
   d.tiles = tiles; d.tile_count = tile_count; d.M = M;
   d.n_col_tiles = ceil_div(H, 64);
-  KernelTimer timer(ctx, k_down, stream);
+  KernelTimer timer(ctx, K_DOWN, stream);
   return launch_gemm_f32<false>(ctx, d, max_m_tiles, stream);
 }
 
@@ -133,12 +135,13 @@ int launch_expert_ffn(revive_ctx* ctx, const void* x_perm, const int32_t* slot_o
     REVIVE_HIP(ctx, hipGetLastError());
   }
   const int bound = max_tiles(N, ctx->P, tile_m);
-  auto pair = bf16 ? bf16_gemm_pair : f32_gemm_pair;
-  int rc = pair(ctx, x_perm, w_gate_up, nullptr, w_down, nullptr, h, y_perm, c.I, tiles, tile_count, 0, bound,
-                REVIVE_K_FFN_GATE_UP, REVIVE_K_FFN_DOWN, stream);
+  constexpr int GU = REVIVE_K_FFN_GATE_UP, DN = REVIVE_K_FFN_DOWN, SGU = REVIVE_K_FFN_SHARED_GATE_UP, SDN = REVIVE_K_FFN_SHARED_DOWN;
+  int rc = bf16 ? bf16_gemm_pair<GU, DN>(ctx, x_perm, w_gate_up, nullptr, w_down, nullptr, h, y_perm, c.I, tiles, tile_count, 0, bound, stream)
+                : f32_gemm_pair<GU, DN>(ctx, x_perm, w_gate_up, nullptr, w_down, nullptr, h, y_perm, c.I, tiles, tile_count, 0, bound, stream);
   if (rc != REVIVE_OK || !y_shared) return rc;
-  return pair(ctx, x, nullptr, w_sh_gate_up, nullptr, w_sh_down, h_shared, y_shared, c.I_shared, nullptr, nullptr, T,
-              ceil_div(T, tile_m), REVIVE_K_FFN_SHARED_GATE_UP, REVIVE_K_FFN_SHARED_DOWN, stream);
+  const int dense_tiles = ceil_div(T, tile_m);
+  return bf16 ? bf16_gemm_pair<SGU, SDN>(ctx, x, nullptr, w_sh_gate_up, nullptr, w_sh_down, h_shared, y_shared, c.I_shared, nullptr, nullptr, T, dense_tiles, stream)
+              : f32_gemm_pair<SGU, SDN>(ctx, x, nullptr, w_sh_gate_up, nullptr, w_sh_down, h_shared, y_shared, c.I_shared, nullptr, nullptr, T, dense_tiles, stream);
 }
 
 }  // namespace revive

@@ -60,7 +60,8 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
 
 __device__ __forceinline__ float silu_f32(float z) { return z / (1.0f + __expf(-z)); }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
+// KID (the library's kernel id) only gives each use of the kernel its own symbol name in profiles.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int KID>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmArgs g) {
   constexpr int NT = 64 * WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
@@ -245,11 +246,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
 }
 
 // Launch helper: grid covers `max_m_tiles` row-tiles (an upper bound; surplus workgroups exit).
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int KID>
 int launch_gemm_bf16(revive_ctx* ctx, const GemmArgs& args, int max_m_tiles, hipStream_t stream) {
   constexpr int NT = 64 * WAVES_M * WAVES_N;
   constexpr size_t lds = 2 * (BM + BN) * 128;
-  auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, EPI>;
+  auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, EPI, KID>;
   static bool configured = false;  // per instantiation
   if (!configured) {
     REVIVE_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,

@@ -158,7 +158,7 @@ int launch_router_gemm(revive_ctx* ctx, const void* x, const void* w, float* log
     a.tiles = nullptr; a.tile_count = nullptr; a.M = T;
     constexpr int BM = 128, BN = 64;
     a.n_col_tiles = ceil_div(c.E, BN);
-    return launch_gemm_bf16<BM, BN, 4, 1, EPI_F32>(ctx, a, ceil_div(T, BM), stream);
+    return launch_gemm_bf16<BM, BN, 4, 1, EPI_F32, REVIVE_K_ROUTER_GEMM>(ctx, a, ceil_div(T, BM), stream);
   }
   GemmF32Args a{};
   a.A = static_cast<const float*>(x); a.lda = c.H;

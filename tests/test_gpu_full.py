@@ -1,0 +1,203 @@
+"""GPU parity at the full workload sizes, in the launch configuration the benchmark times.
+
+The integer stages are compared in full with the oracle (fed the GPU's fp32 logits).  The fp64
+expert FFN is too slow on the CPU at these sizes, so values are compared on samples the oracle
+computes one by one: all rows of a few slots (one serving a degraded expert among them) and the
+complete layer output of a few tokens (tokens that would have used a lost expert among them),
+plus properties that hold at any size."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import revive_oracle as orc
+from harness import GpuLayer, TOL, compare_selection, f64, rel_err
+
+pytestmark = pytest.mark.gpu
+
+FULL = ["c2", "c3", "c4", "c5"]
+N_SAMPLE_TOKENS = 10
+N_SAMPLE_SLOTS = 3
+
+
+def _i(t):
+    return t.cpu().numpy()
+
+
+@pytest.fixture(scope="module", params=FULL)
+def full_layer(request):
+    cfg = synth.get_config(request.param)
+    print(f"building {cfg.name} on the GPU", flush=True)
+    g = GpuLayer(cfg)
+    g.result = g.forward()
+    torch.cuda.synchronize()
+    yield g
+    g.close()
+    del g
+    torch.cuda.empty_cache()
+
+
+def test_integer_stages_full(full_layer):
+    g = full_layer
+    c, r = g.cfg, g.result
+    m = g.oracle_map()
+    lg = f64(r["logits"])
+    s = orc.scores(lg, c.score_fn)
+    sel = orc.masked_selection_scores(s, m.l2p_count)
+    ref_l = orc.select_topk(sel, c.k, c.n_group, c.topk_group)
+    assert np.array_equal(_i(r["topk_logical"]), ref_l)
+    ref_p = orc.remap(ref_l, m)
+    assert np.array_equal(_i(r["topk_phys"]), ref_p)
+    ref_w = orc.gate_weights(s, ref_l)
+    assert np.abs(f64(r["topk_weight"]) - ref_w).max() < 2e-7
+    assert np.abs(f64(r["topk_weight"]).sum(axis=1) - 1.0).max() < 1e-6
+    offs, dst, src = orc.dispatch_indices(ref_p, c.P)
+    assert np.array_equal(_i(r["slot_offsets"]), offs)
+    assert np.array_equal(_i(r["dst_row"]), dst) and np.array_equal(_i(r["src_of"]), src)
+    # properties: every routed row lands once on a live slot, failed ranks receive nothing
+    assert offs[-1] == c.T * c.k and m.slot_alive[ref_p].all()
+    S = c.slots_per_rank
+    for f in np.nonzero(g.failed)[0]:
+        assert offs[(f + 1) * S] - offs[f * S] == 0
+    # the permuted rows are exact copies
+    rows = torch.from_numpy(src // c.k).to(g.device).long()
+    assert torch.equal(r["x_perm"], g.x[rows])
+
+
+def test_router_logits_full(full_layer):
+    g = full_layer
+    c, r = g.cfg, g.result
+    ref_lg = orc.router_logits(f64(g.x), f64(g.w_router))
+    assert rel_err(f64(r["logits"]), ref_lg) < 1e-5
+    m = g.oracle_map()
+    sel = orc.masked_selection_scores(orc.scores(ref_lg, c.score_fn), m.l2p_count)
+    # compare on a bounded sample of tokens (the fp64 selection is a Python loop)
+    rng = np.random.default_rng(1)
+    toks = np.sort(rng.choice(c.T, size=min(c.T, 4096), replace=False))
+    ref = orc.select_topk(sel[toks], c.k, c.n_group, c.topk_group)
+    near, bad = compare_selection(c, _i(r["topk_logical"])[toks], sel[toks], ref)
+    print(f"[{c.name}] own-logits selection: near-ties {len(near)} of {len(toks)} tokens, mismatches {len(bad)}")
+    assert not bad
+
+
+def test_sampled_values_full(full_layer):
+    g = full_layer
+    c, r = g.cfg, g.result
+    m = g.oracle_map()
+    tol = TOL[c.dtype]
+    rng = np.random.default_rng(2)
+    offs = _i(r["slot_offsets"])
+    counts = np.diff(offs)
+    full_m = orc.build_map(g.p2l, synth.failed_mask(c, []), c.slots_per_rank, c.E, c.max_replicas)
+
+    # --- all rows of a few live slots: one that serves a degraded expert, one of a two-replica expert
+    degraded = [e for e in range(c.E) if 0 < m.l2p_count[e] < full_m.l2p_count[e]]
+    two = [e for e in range(c.E) if m.l2p_count[e] >= 2]
+    slots = []
+    if degraded:
+        slots.append(int(m.l2p_table[degraded[0], 0]))
+    if two:
+        slots.append(int(m.l2p_table[two[0], 1]))
+    live = np.nonzero((m.slot_alive == 1) & (counts > 0))[0]
+    while len(slots) < N_SAMPLE_SLOTS:
+        p = int(rng.choice(live))
+        if p not in slots:
+            slots.append(p)
+    worst = 0.0
+    for p in slots:
+        a, b = int(offs[p]), int(offs[p + 1])
+        if b == a:
+            continue
+        w = g.slot_expert_f64(p)
+        ref = orc.swiglu_ffn(f64(r["x_perm"][a:b]), w["gate"], w["up"], w["down"])
+        worst = max(worst, rel_err(f64(r["y_perm"][a:b]), ref))
+    print(f"[{c.name}] y_perm on slots {slots}: rel err {worst:.2e}")
+    assert worst < tol
+
+    # --- the complete output of a few tokens, from the definition of the layer
+    s_all = orc.scores(f64(r["logits"]), c.score_fn)
+    lost = np.nonzero(m.l2p_count == 0)[0]
+    toks = []
+    if lost.size:   # tokens whose unmasked choice would have contained a lost expert
+        plain = orc.select_topk(s_all[:2048], c.k, c.n_group, c.topk_group)
+        hit = np.nonzero(np.isin(plain, lost).any(axis=1))[0]
+        toks += [int(t) for t in hit[:3]]
+    while len(toks) < N_SAMPLE_TOKENS:
+        t = int(rng.integers(c.T))
+        if t not in toks:
+            toks.append(t)
+    toks = np.array(toks)
+    top = _i(r["topk_logical"])[toks]
+    wts = orc.gate_weights(s_all[toks], top)
+    xs = f64(g.x[torch.from_numpy(toks).to(g.device)])
+    ref_out = np.zeros((len(toks), c.H))
+    for e in np.unique(top):
+        w = g.expert_f64(int(e))
+        for a in range(len(toks)):
+            for j in range(c.k):
+                if top[a, j] == e:
+                    ref_out[a] += wts[a, j] * orc.swiglu_ffn(xs[a:a + 1], w["gate"], w["up"], w["down"])[0]
+        del w
+    sh = g.shared_f64()
+    if sh is not None:
+        ref_sh = orc.swiglu_ffn(xs, sh["gate"], sh["up"], sh["down"])
+        ref_out += ref_sh
+        e_sh = rel_err(f64(r["y_shared"][torch.from_numpy(toks).to(g.device)]), ref_sh)
+        assert e_sh < tol
+    e_out = rel_err(f64(r["out"][torch.from_numpy(toks).to(g.device)]), ref_out)
+    print(f"[{c.name}] out on tokens {toks.tolist()}: rel err {e_out:.2e}")
+    assert e_out < tol
+    assert not np.isin(top, lost).any()
+
+
+def test_graph_replay_across_a_mask_flip():
+    """The prefill-chunk workload: the mask flips from no failure to two failed ranks between two
+    replays of one captured graph; the executable is unchanged and both results match the oracle
+    evaluated under the map that was in force."""
+    cfg = synth.get_config("c5")
+    g = GpuLayer(cfg, failed=[])
+    try:
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            g.forward(stream=stream)
+            stream.synchronize()
+            g.capture(stream)
+            exec_id = g.layer.graph_exec_id(g.graph)
+            for phase, failed in (("before", []), ("after", list(cfg.failed_ranks)), ("restored", [])):
+                stats = g.set_failed(failed, stream=stream)
+                for _ in range(2):          # replay twice with a synchronisation in between
+                    g.replay(stream)
+                    stream.synchronize()
+                assert g.layer.graph_exec_id(g.graph) == exec_id
+                r = g.buf
+                m = g.oracle_map()
+                assert stats["n_lost_experts"] == m.n_lost_experts
+                s = orc.scores(f64(r["logits"]), cfg.score_fn)
+                rng = np.random.default_rng(3)
+                toks = np.sort(rng.choice(cfg.T, size=2048, replace=False))
+                ref_l = orc.select_topk(orc.masked_selection_scores(s[toks], m.l2p_count), cfg.k)
+                assert np.array_equal(_i(r["topk_logical"])[toks], ref_l)
+                phys = _i(r["topk_phys"])
+                ref_p = np.stack([[m.l2p_table[e, t % m.l2p_count[e]] for e in row] for t, row in zip(toks, ref_l)])
+                assert np.array_equal(phys[toks], ref_p)
+                assert m.slot_alive[phys].all()
+                offs, dst, src = orc.dispatch_indices(phys, cfg.P)
+                assert np.array_equal(_i(r["slot_offsets"]), offs) and np.array_equal(_i(r["dst_row"]), dst)
+                # complete output of a few tokens under this map
+                sample = toks[:4]
+                top = ref_l[:4]
+                wts = orc.gate_weights(s[sample], top)
+                xs = f64(g.x[torch.from_numpy(sample).to(g.device)])
+                ref_out = np.zeros((len(sample), cfg.H))
+                for a in range(len(sample)):
+                    for j in range(cfg.k):
+                        w = g.expert_f64(int(top[a, j]))
+                        ref_out[a] += wts[a, j] * orc.swiglu_ffn(xs[a:a + 1], w["gate"], w["up"], w["down"])[0]
+                sh = g.shared_f64()
+                ref_out += orc.swiglu_ffn(xs, sh["gate"], sh["up"], sh["down"])
+                err = rel_err(f64(r["out"][torch.from_numpy(sample).to(g.device)]), ref_out)
+                print(f"[c5 graph {phase}] lost={stats['n_lost_experts']} out rel err {err:.2e}", flush=True)
+                assert err < TOL[cfg.dtype]
+    finally:
+        g.close()
+        torch.cuda.empty_cache()

@@ -205,3 +205,36 @@ def test_empty_and_single_token():
         assert rel_err(f64(out[:1]), tr.out) < TOL[cfg.dtype]
     finally:
         g.close()
+
+
+def test_graph_replay_matches_eager_across_mask_flips():
+    """One captured graph, replayed after map updates: same executable, results equal to the eager
+    calls and to the oracle under the map in force (Sec. 3.6: no recompilation on recovery)."""
+    cfg = SMALL["c5s"]
+    g = GpuLayer(cfg, failed=[])
+    try:
+        experts = _experts_f64(g)
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            g.forward(stream=stream)
+            stream.synchronize()
+            g.capture(stream)
+            exec_id = g.layer.graph_exec_id(g.graph)
+            for failed in ([], list(cfg.failed_ranks), [0], []):
+                g.set_failed(failed, stream=stream)
+                for rep in range(3):
+                    g.buf["out"].zero_()
+                    g.replay(stream)
+                    stream.synchronize()
+                    out_graph = g.buf["out"].clone()
+                    tr = orc.layer_staged(f64(g.x), None, experts, g.shared_f64(), g.p2l, g.oracle_map(), cfg.k,
+                                          cfg.score_fn, logits=f64(g.buf["logits"]))
+                    assert np.array_equal(_i(g.buf["topk_phys"]), tr.topk_phys)
+                    assert np.array_equal(_i(g.buf["dst_row"]), tr.dst_row)
+                    assert rel_err(f64(out_graph), tr.out) < TOL[cfg.dtype]
+                    g.forward(stream=stream)          # the program's own eager work between replays
+                    stream.synchronize()
+                    assert torch.equal(g.buf["out"], out_graph)
+                assert g.layer.graph_exec_id(g.graph) == exec_id
+    finally:
+        g.close()
