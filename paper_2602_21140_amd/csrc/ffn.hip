@@ -57,7 +57,8 @@ __global__ __launch_bounds__(kMaxP) void ffn_tiles_kernel(const int32_t* __restr
   }
 }
 
-// Tile shapes of the bf16 GEMMs: 256 x 256 x 64 per workgroup of 8 wavefronts (2 x 4).
+// Tile shapes of the bf16 GEMMs: 256 x 256 outputs per workgroup of 8 wavefronts (2 x 4), K in
+// steps of 32 through a four-stage ring of asynchronous global->LDS copies.
 constexpr int kBM = kTileM_bf16, kBN = 256, kWM = 2, kWN = 4;
 
 template <int K_GATE_UP, int K_DOWN>
@@ -74,7 +75,7 @@ int bf16_gemm_pair(revive_ctx* ctx, const void* A, const void* const* gu_tab, co
   a.n_col_tiles = ceil_div(I, kBN / 2);
   {
     KernelTimer timer(ctx, K_GATE_UP, stream);
-    int rc = launch_gemm_bf16<kBM, kBN, kWM, kWN, EPI_SWIGLU, K_GATE_UP>(ctx, a, max_m_tiles, stream);
+    int rc = launch_gemm_bf16<kBM, kBN, kWM, kWN, EPI_SWIGLU, K_GATE_UP, true>(ctx, a, max_m_tiles, stream);
     if (rc != REVIVE_OK) return rc;
   }
   GemmArgs d{};
@@ -85,7 +86,7 @@ int bf16_gemm_pair(revive_ctx* ctx, const void* A, const void* const* gu_tab, co
   d.tiles = tiles; d.tile_count = tile_count; d.M = M;
   d.n_col_tiles = ceil_div(H, kBN);
   KernelTimer timer(ctx, K_DOWN, stream);
-  return launch_gemm_bf16<kBM, kBN, kWM, kWN, EPI_BF16, K_DOWN>(ctx, d, max_m_tiles, stream);
+  return launch_gemm_bf16<kBM, kBN, kWM, kWN, EPI_BF16, K_DOWN, true>(ctx, d, max_m_tiles, stream);
 }
 
 template <int K_GATE_UP, int K_DOWN>

@@ -14,12 +14,14 @@
 // walked in steps of 64: the next step's global loads are issued into registers before the MFMAs
 // of the current step and written to the other half of a double-buffered LDS tile afterwards, one
 // barrier per step.  LDS rows are 128 bytes (64 bf16); the 16-byte chunk index is XOR-ed with
-// (row & 7) so that both the 16-byte writes and the per-lane 16-byte fragment reads are
-// conflict-free.  The weights go in as the MFMA's first operand so that each lane ends up with
+// ((row >> 1) & 7) so that both the 16-byte writes and the per-lane 16-byte fragment reads are
+// conflict-free on the 64-bank LDS.  The weights go in as the MFMA's first operand so that each lane ends up with
 // four consecutive output columns of one activation row, which it stores as one 8/16-byte word.
 #pragma once
 
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "ctx.hpp"
 
@@ -30,6 +32,13 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+// Pointers that are known to address HBM: lets the compiler emit global_load/global_store
+// instead of flat accesses (which also tick the LDS counter and so serialise with LDS waits).
+typedef const __attribute__((address_space(1))) u32x4* gptr_u32x4;
+
+__device__ __forceinline__ u32x4 load_global_16B(const unsigned char* p) {
+  return *reinterpret_cast<gptr_u32x4>(reinterpret_cast<uintptr_t>(p));
+}
 
 enum { EPI_F32 = 0, EPI_BF16 = 1, EPI_SWIGLU = 2 };
 
@@ -57,6 +66,12 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
   u += 0x7FFFu + ((u >> 16) & 1u);
   return u >> 16;
 }
+
+// LDS swizzle.  The gfx950 LDS has 64 four-byte banks (256 B per clock) and serves a 16-byte
+// per-lane access in groups of 16 lanes.  Tile rows are 128 bytes, so rows r and r+2 start on the
+// same bank; XOR-ing the 16-byte chunk index with (row >> 1) & 7 makes the 16 rows a lane group
+// touches (same logical chunk) fall on 16 distinct 16-byte bank groups.
+__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
 __device__ __forceinline__ float silu_f32(float z) { return z / (1.0f + __expf(-z)); }
 
@@ -113,7 +128,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
     const int idx = it * NT + tid, row = idx >> 3, chunk = idx & 7;
     const int grow = min(row_begin + row, row_end - 1);  // rows past the tile re-read its last row
     a_src[it] = Abase + (static_cast<int64_t>(grow) * g.lda + chunk * 8) * 2;
-    a_dst[it] = row * 128 + ((chunk ^ (row & 7)) << 4);
+    a_dst[it] = row * 128 + ((chunk ^ swz(row)) << 4);
   }
 #pragma unroll
   for (int it = 0; it < ITER_B; ++it) {
@@ -127,7 +142,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
       brow = min(n0 + row, g.n_out - 1);
     }
     b_src[it] = Bbase + (static_cast<int64_t>(brow) * g.ldb + chunk * 8) * 2;
-    b_dst[it] = BM * 128 + row * 128 + ((chunk ^ (row & 7)) << 4);
+    b_dst[it] = BM * 128 + row * 128 + ((chunk ^ swz(row)) << 4);
   }
 
   // ---- per-lane LDS fragment addresses (without the k-step part)
@@ -158,9 +173,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
   auto load_global = [&](int kt) {
     const int64_t koff = static_cast<int64_t>(kt) * 128;  // 64 bf16
 #pragma unroll
-    for (int it = 0; it < ITER_A; ++it) a_reg[it] = *reinterpret_cast<const u32x4*>(a_src[it] + koff);
+    for (int it = 0; it < ITER_A; ++it) a_reg[it] = load_global_16B(a_src[it] + koff);
 #pragma unroll
-    for (int it = 0; it < ITER_B; ++it) b_reg[it] = *reinterpret_cast<const u32x4*>(b_src[it] + koff);
+    for (int it = 0; it < ITER_B; ++it) b_reg[it] = load_global_16B(b_src[it] + koff);
   };
   auto store_lds = [&](int stage) {
     unsigned char* base = smem + stage * STAGE;
@@ -170,36 +185,55 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
     for (int it = 0; it < ITER_B; ++it) *reinterpret_cast<u32x4*>(base + b_dst[it]) = b_reg[it];
   };
 
+  // Fragment loads of one 16-wide k-step from an LDS stage.
+  auto load_frags = [&](const unsigned char* base, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
+    const int chunk = ks * 2 + (lane >> 5);
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+      const int r = a_frag[tm];
+      af[tm] = *reinterpret_cast<const bf16x8*>(base + r * 128 + ((chunk ^ swz(r)) << 4));
+    }
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+      const int r = b_frag[tn];
+      bfr[tn] = *reinterpret_cast<const bf16x8*>(base + r * 128 + ((chunk ^ swz(r)) << 4));
+    }
+  };
+  auto mfma_step = [&](const bf16x8 (&af)[TM], const bf16x8 (&bfr)[TN]) {
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn)
+        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tn], af[tm], acc[tm][tn], 0, 0, 0);
+  };
+
+  // Software pipeline: the fragments of k-step s+1 are read from LDS while the MFMAs of step s
+  // run; the next K-tile (already in registers) is written to the other LDS stage and the
+  // workgroup synchronised *before* the last k-step's MFMAs, so that the first fragments of the
+  // next stage are in flight while those MFMAs execute.
   const int KT = g.K >> 6;
+  bf16x8 af0[TM], bf0[TN], af1[TM], bf1[TN];
   load_global(0);
   store_lds(0);
   __syncthreads();
+  if (KT > 1) load_global(1);
+  load_frags(smem, 0, af0, bf0);
 
   for (int kt = 0; kt < KT; ++kt) {
-    if (kt + 1 < KT) load_global(kt + 1);
-    const unsigned char* base = smem + (kt & 1) * STAGE;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const int chunk = ks * 2 + (lane >> 5);
-      bf16x8 af[TM], bfr[TN];
-#pragma unroll
-      for (int tm = 0; tm < TM; ++tm) {
-        const int r = a_frag[tm];
-        af[tm] = *reinterpret_cast<const bf16x8*>(base + r * 128 + ((chunk ^ (r & 7)) << 4));
-      }
-#pragma unroll
-      for (int tn = 0; tn < TN; ++tn) {
-        const int r = b_frag[tn];
-        bfr[tn] = *reinterpret_cast<const bf16x8*>(base + r * 128 + ((chunk ^ (r & 7)) << 4));
-      }
-#pragma unroll
-      for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
-          acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tn], af[tm], acc[tm][tn], 0, 0, 0);
+    const unsigned char* cur = smem + (kt & 1) * STAGE;
+    load_frags(cur, 1, af1, bf1);
+    mfma_step(af0, bf0);
+    load_frags(cur, 2, af0, bf0);
+    mfma_step(af1, bf1);
+    load_frags(cur, 3, af1, bf1);
+    mfma_step(af0, bf0);
+    if (kt + 1 < KT) {
+      store_lds((kt + 1) & 1);
+      if (kt + 2 < KT) load_global(kt + 2);
+      __syncthreads();
+      load_frags(smem + ((kt + 1) & 1) * STAGE, 0, af0, bf0);
     }
-    if (kt + 1 < KT) store_lds((kt + 1) & 1);
-    __syncthreads();
+    mfma_step(af1, bf1);
   }
 
   // ---- epilogue.  Lane holds, per 32x32 tile, for q = 0..3 the four columns
@@ -245,12 +279,273 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
   }
 }
 
-// Launch helper: grid covers `max_m_tiles` row-tiles (an upper bound; surplus workgroups exit).
+// ---------------------------------------------------------------------------------------------
+// Variant with asynchronous global->LDS copies (global_load_lds_dwordx4) and a four-stage ring.
+//
+// Same contract and output layout as gemm_bf16_kernel.  K is walked in steps of 32; a stage holds
+// a BM x 32 tile of A and a BN x 32 tile of B (64-byte rows).  The copy of K-step t+3 is issued
+// while step t is being multiplied, so three steps (about 1.3 us of MFMA work at full rate) are
+// in flight to cover HBM latency, and no register is spent on staging.  Per K-step there is one
+// workgroup barrier, placed before the last 16-wide half-step's MFMAs so that the first fragment
+// reads of the next stage overlap them.
+//
+// LDS layout of a stage: row r at r*64 bytes, its four 16-byte chunks stored at chunk ^ ((r>>2)&3):
+// a copy instruction writes lane l's 16 bytes to (its 1 KiB window) + 16*l, i.e. 16 rows per
+// wavefront instruction, and each lane fetches the chunk that belongs in its slot; the fragment
+// reads (16 lanes = 16 consecutive rows, same logical chunk) then cover all 64 banks once.
+// s_waitcnt immediate (gfx9 encoding) for "vmcnt(vm) lgkmcnt(0)", export counter ignored.
+__host__ __device__ constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 0xF) | ((vm >> 4) << 14) | (0x7 << 4) | (0 << 8); }
+
+__device__ __forceinline__ int swz32(int row) { return (row >> 2) & 3; }
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int KID>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(GemmArgs g) {
+  constexpr int NT = 64 * WAVES_M * WAVES_N, NW = WAVES_M * WAVES_N;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int BN_OUT = EPI == EPI_SWIGLU ? BN / 2 : BN;
+  constexpr int STAGES = 4;
+  constexpr int STAGE = (BM + BN) * 64;       // bytes
+  constexpr int CP_A = BM / 16 / NW, CP_B = BN / 16 / NW;  // copy instructions per wavefront and stage
+  constexpr int CP = CP_A + CP_B;
+  static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "copy split");
+  static_assert(TM <= 4, "row sub-tile dispatch below covers up to four");
+  static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU needs gate and up tiles in one wave");
+  typedef __attribute__((address_space(1))) const void* gptr;
+  typedef __attribute__((address_space(3))) void* lptr;
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+  const int n_m_tiles = g.tiles ? *g.tile_count : (g.M + BM - 1) / BM;
+  const int total = n_m_tiles * g.n_col_tiles;
+  const int per_xcd = (total + 7) >> 3;
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int logical = xcd * per_xcd + local;
+  if (local >= per_xcd || logical >= total) return;
+  const int m_idx = logical / g.n_col_tiles;
+  const int n_idx = logical - m_idx * g.n_col_tiles;
+
+  int group = 0, row_begin, row_end;
+  if (g.tiles) {
+    const MTile t = g.tiles[m_idx];
+    group = t.group;
+    row_begin = t.row_begin;
+    row_end = t.row_end;
+  } else {
+    row_begin = m_idx * BM;
+    row_end = min(g.M, row_begin + BM);
+  }
+  const unsigned char* Bbase = static_cast<const unsigned char*>(g.B_tab ? g.B_tab[group] : g.B_one);
+  const unsigned char* Abase = static_cast<const unsigned char*>(g.A);
+  const int n0 = n_idx * BN_OUT;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+  // ---- copy plan: instruction i of this wavefront fills rows [(wave*CP_x + i)*16, +16) of the A
+  // (then B) part of a stage; lane l owns row l/4 of those, physical chunk l%4.
+  const unsigned char* cp_src[CP];
+  int cp_dst[CP];  // wavefront-uniform LDS offset of the 1 KiB window inside a stage
+#pragma unroll
+  for (int i = 0; i < CP; ++i) {
+    const bool isA = i < CP_A;
+    const int blk = isA ? wave * CP_A + i : wave * CP_B + (i - CP_A);
+    const int row = blk * 16 + (lane >> 2);
+    const int chunk = (lane & 3) ^ swz32(row);
+    if (isA) {
+      const int grow = min(row_begin + row, row_end - 1);
+      cp_src[i] = Abase + (static_cast<int64_t>(grow) * g.lda + chunk * 8) * 2;
+      cp_dst[i] = blk * 1024;
+    } else {
+      int brow;
+      if (EPI == EPI_SWIGLU) {
+        const int half = row >= BN / 2;
+        const int col = min(n0 + row - half * (BN / 2), g.n_out - 1);
+        brow = col + half * g.n_out;
+      } else {
+        brow = min(n0 + row, g.n_out - 1);
+      }
+      cp_src[i] = Bbase + (static_cast<int64_t>(brow) * g.ldb + chunk * 8) * 2;
+      cp_dst[i] = BM * 64 + blk * 1024;
+    }
+  }
+  // The copy is written as inline assembly on purpose: the compiler's wait-count bookkeeping treats
+  // a global_load_lds it knows about as "may touch both memory and LDS" and from then on turns
+  // every LDS wait into a full drain, which would undo the software pipeline.  Issued this way the
+  // copies are invisible to that bookkeeping and are waited for explicitly before each barrier.
+  const uint32_t smem_lds = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lptr)smem));
+  auto issue_copy = [&](int kt) {
+    const uint32_t stage = smem_lds + (kt & (STAGES - 1)) * STAGE;
+    const int64_t koff = static_cast<int64_t>(kt) * 64;  // 32 bf16
+#pragma unroll
+    for (int i = 0; i < CP; ++i) {
+      const unsigned char* src = cp_src[i] + koff;
+      const uint32_t dst = __builtin_amdgcn_readfirstlane(stage + cp_dst[i]);
+      asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(dst) : "memory", "m0");
+    }
+  };
+
+  // ---- per-lane fragment rows
+  int a_frag[TM], b_frag[TN];
+  // 32-row sub-tiles are dealt round-robin to the wavefront rows (sub-tile tm*WAVES_M + wm), so a
+  // ragged row-tile keeps every wavefront equally busy.
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm) a_frag[tm] = (tm * WAVES_M + wm) * 32 + (lane & 31);
+#pragma unroll
+  for (int tn = 0; tn < TN; ++tn) {
+    int r;
+    if (EPI == EPI_SWIGLU) {
+      const int half = tn >= TN / 2;
+      r = half * (BN / 2) + wn * (WN / 2) + (tn - half * (TN / 2)) * 32 + (lane & 31);
+    } else {
+      r = wn * WN + tn * 32 + (lane & 31);
+    }
+    b_frag[tn] = BM + r;
+  }
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0.f;
+
+  // A ragged row-tile leaves some 32-row sub-tiles of a wavefront without any valid row; the
+  // main loop is instantiated for each count of valid sub-tiles so that those MFMAs (and their
+  // fragment reads) are not issued at all.  The wavefront still takes part in copies and barriers.
+  const int KT = g.K >> 5;
+  const int n_sub = (row_end - row_begin + 31) >> 5;  // sub-tiles holding at least one valid row
+  const int tm_valid = min(TM, max(0, (n_sub - wm + WAVES_M - 1) / WAVES_M));
+
+  auto run = [&](auto tmv_tag) {
+    constexpr int TMV = decltype(tmv_tag)::value;
+    auto load_frags = [&](const unsigned char* base, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
+      if (TMV == 0) return;
+      const int chunk = ks * 2 + (lane >> 5);
+#pragma unroll
+      for (int tm = 0; tm < TMV; ++tm) {
+        const int r = a_frag[tm];
+        af[tm] = *reinterpret_cast<const bf16x8*>(base + r * 64 + ((chunk ^ swz32(r)) << 4));
+      }
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) {
+        const int r = b_frag[tn];
+        bfr[tn] = *reinterpret_cast<const bf16x8*>(base + r * 64 + ((chunk ^ swz32(r)) << 4));
+      }
+    };
+    auto mfma_step = [&](const bf16x8 (&af)[TM], const bf16x8 (&bfr)[TN]) {
+#pragma unroll
+      for (int tm = 0; tm < TMV; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+          acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tn], af[tm], acc[tm][tn], 0, 0, 0);
+    };
+    // One K-step.  COPY: issue the copy of step kt+3.  VM: copies that may stay pending at the
+    // barrier (those of the steps after kt+1).  LAST: no next stage to publish.
+    bf16x8 af0[TM], bf0[TN], af1[TM], bf1[TN];
+    auto step = [&](int kt, auto copy_tag, auto vm_tag, auto last_tag) {
+      constexpr bool COPY = decltype(copy_tag)::value, LAST = decltype(last_tag)::value;
+      constexpr int VM = decltype(vm_tag)::value;
+      const unsigned char* cur = smem + (kt & (STAGES - 1)) * STAGE;
+      // stage (kt+3)%4 held step kt-1, which every wavefront finished reading before the last barrier
+      if (COPY) issue_copy(kt + 3);
+      load_frags(cur, 1, af1, bf1);
+      __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the MFMAs they overlap with
+      mfma_step(af0, bf0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (!LAST) {
+        // this wavefront's copies of step kt+1 have landed once only VM newer copies are pending;
+        // all its fragment reads of the current stage have returned (lgkmcnt 0)
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(VM));
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        load_frags(smem + ((kt + 1) & (STAGES - 1)) * STAGE, 0, af0, bf0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      mfma_step(af1, bf1);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    using T = std::true_type;
+    using F = std::false_type;
+    load_frags(smem, 0, af0, bf0);
+    int kt = 0;
+    for (; kt + 3 < KT; ++kt) step(kt, T{}, std::integral_constant<int, 2 * CP>{}, F{});
+    if (kt + 2 < KT) { step(kt, F{}, std::integral_constant<int, CP>{}, F{}); ++kt; }
+    if (kt + 1 < KT) { step(kt, F{}, std::integral_constant<int, 0>{}, F{}); ++kt; }
+    step(kt, F{}, std::integral_constant<int, 0>{}, T{});
+  };
+
+  issue_copy(0);
+  if (KT > 1) issue_copy(1);
+  if (KT > 2) issue_copy(2);
+  asm volatile("" ::: "memory");
+  if (KT > 2) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * CP));
+  else if (KT > 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(CP));
+  else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+
+  switch (tm_valid) {
+    case 0: run(std::integral_constant<int, 0>{}); break;
+    case 1: run(std::integral_constant<int, 1>{}); break;
+    case 2: run(std::integral_constant<int, (TM >= 2 ? 2 : TM)>{}); break;
+    case 3: run(std::integral_constant<int, (TM >= 3 ? 3 : TM)>{}); break;
+    default: run(std::integral_constant<int, TM>{}); break;
+  }
+
+  // ---- epilogue.  Lane holds, per 32x32 tile, for q = 0..3 the four columns
+  // q*8 + (lane/32)*4 + {0..3} of activation row lane % 32.
+  constexpr int TN_OUT = EPI == EPI_SWIGLU ? TN / 2 : TN;
+  constexpr int WN_OUT = EPI == EPI_SWIGLU ? WN / 2 : WN;
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm) {
+    const int row = row_begin + (tm * WAVES_M + wm) * 32 + (lane & 31);
+    if (row >= row_end) continue;
+#pragma unroll
+    for (int tn = 0; tn < TN_OUT; ++tn) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = n0 + wn * WN_OUT + tn * 32 + q * 8 + (lane >> 5) * 4;
+        if (col >= g.n_out) continue;
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          if (EPI == EPI_SWIGLU) v[r] = silu_f32(acc[tm][tn][q * 4 + r]) * acc[tm][tn + TN / 2][q * 4 + r];
+          else v[r] = acc[tm][tn][q * 4 + r];
+        }
+        const int64_t off = static_cast<int64_t>(row) * g.ldc + col;
+        if (col + 3 < g.n_out && (g.ldc & 3) == 0) {
+          if (EPI == EPI_F32) {
+            f32x4 o = {v[0], v[1], v[2], v[3]};
+            *reinterpret_cast<f32x4*>(static_cast<float*>(g.C) + off) = o;
+          } else {
+            u32x2 o = {f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16),
+                       f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16)};
+            *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(g.C) + off) = o;
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            if (col + r >= g.n_out) break;
+            if (EPI == EPI_F32) static_cast<float*>(g.C)[off + r] = v[r];
+            else static_cast<uint16_t*>(g.C)[off + r] = static_cast<uint16_t>(f32_to_bf16_bits(v[r]));
+          }
+        }
+      }
+    }
+  }
+}
+
+// Launch helper: grid covers `max_m_tiles` row-tiles (an upper bound; surplus workgroups exit).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int KID, bool DMA = false>
 int launch_gemm_bf16(revive_ctx* ctx, const GemmArgs& args, int max_m_tiles, hipStream_t stream) {
   constexpr int NT = 64 * WAVES_M * WAVES_N;
-  constexpr size_t lds = 2 * (BM + BN) * 128;
-  auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, EPI, KID>;
+  constexpr size_t lds = DMA ? 4 * (BM + BN) * 64 : 2 * (BM + BN) * 128;
+  void (*kern)(GemmArgs);
+  if constexpr (DMA) kern = gemm_bf16_dma_kernel<BM, BN, WAVES_M, WAVES_N, EPI, KID>;
+  else kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, EPI, KID>;
   static bool configured = false;  // per instantiation
   if (!configured) {
     REVIVE_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
