@@ -87,6 +87,9 @@ def main():
     ap.add_argument("--workload", default="c2", help="c2 (default, the metric's configuration), c3, c4, c5, c1")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--overlap-shared", action="store_true",
+                    help="run the shared expert on a side stream next to route/dispatch (off by default so that "
+                         "every kernel of the step runs alone and its timing is its own)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (expert-parallel ranks are simulated as rank segments "
@@ -107,9 +110,10 @@ def main():
     K, W = args.steps, args.warmup
 
     with torch.cuda.stream(stream):
-        g.forward(stream=stream)                      # eager pass (also configures the kernels)
+        ov = args.overlap_shared
+        g.forward(stream=stream, overlap_shared=ov)   # eager pass (also configures the kernels)
         stream.synchronize()
-        g.capture(stream)
+        g.capture(stream, overlap_shared=ov)
         exec_id = L.graph_exec_id(g.graph)
         for _ in range(W):
             g.replay(stream)
@@ -126,7 +130,7 @@ def main():
         L.set_kernel_timing(True)
         L.reset_kernel_times()
         for _ in range(K):
-            g.forward(stream=stream)
+            g.forward(stream=stream, overlap_shared=False)
         stream.synchronize()
         times = L.kernel_times()
         L.set_kernel_timing(False)
@@ -188,7 +192,7 @@ def main():
                                f"{cfg.score_fn}" + (f" {cfg.n_group} groups/top-{cfg.topk_group}" if cfg.n_group > 1 else "")
                                + f", {cfg.n_ranks} simulated ranks x {cfg.slots_per_rank} slots, failed ranks "
                                f"{list(cfg.failed_ranks)}",
-                   "map": g.stats, "execution": "one captured graph replayed per step"},
+                   "map": g.stats, "execution": "one captured graph replayed per step" + (", shared expert on a side stream" if ov else "")},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel<SwiGLU> (ffn_gate_up)" if cfg.dtype == "bf16" else "gemm_f32_kernel<SwiGLU>",
                      "achieved": dom_tflops, "peak": peak, "unit": "TFLOP/s", "frac": dom_tflops / peak,
                      "avg_launch_us": avg_us[dom], "flops_per_launch": work["gate_up_flops"], "traffic": None},

@@ -194,6 +194,14 @@ int revive_expert_ffn(revive_ctx* ctx, const void* x_perm, const int32_t* slot_o
                       const void* x, const void* w_sh_gate_up, const void* w_sh_down,
                       void* y_shared, int32_t T, revive_stream stream);
 
+/* a8' - The shared expert alone: y_shared = (silu(x G_s) * (x U_s)) D_s on all T
+ * rows of x.  It depends on nothing that routing produces, so a caller may
+ * enqueue it on a second stream next to route/dispatch and pass y_shared = NULL
+ * to revive_expert_ffn; revive_combine must then be ordered after both streams.
+ * Uses its own part of the workspace (no overlap with revive_expert_ffn's). */
+int revive_shared_ffn(revive_ctx* ctx, const void* x, const void* w_sh_gate_up,
+                      const void* w_sh_down, void* y_shared, int32_t T, revive_stream stream);
+
 /* a9 - Combine / E2A (Sec. 2.3): out[t, :] = sum_j topk_weight[t, j] *
  * y_perm[dst_row[t*k + j], :] (+ y_shared[t, :]); fp32 accumulation in
  * ascending j, shared expert last, one rounding to dtype.

@@ -74,6 +74,7 @@ def lib() -> C.CDLL:
         "revive_route": (C.c_int, [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]),
         "revive_dispatch": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp, vp]),
         "revive_expert_ffn": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]),
+        "revive_shared_ffn": (C.c_int, [vp, vp, vp, vp, vp, i32, vp]),
         "revive_combine": (C.c_int, [vp, vp, vp, vp, vp, i32, vp, vp]),
         "revive_graph_begin": (C.c_int, [vp, vp]),
         "revive_graph_end": (C.c_int, [vp, vp, P(vp)]),
@@ -97,7 +98,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ["revive_create", "revive_destroy", "revive_workspace_bytes", "revive_bind_workspace",
            "revive_set_placement", "revive_update_map", "revive_get_map", "revive_build_map",
-           "revive_route", "revive_dispatch", "revive_expert_ffn", "revive_combine",
+           "revive_route", "revive_dispatch", "revive_expert_ffn", "revive_shared_ffn", "revive_combine",
            "revive_graph_begin", "revive_graph_end", "revive_graph_launch", "revive_graph_exec_id",
            "revive_graph_destroy", "revive_set_kernel_timing", "revive_kernel_time",
            "revive_reset_kernel_times", "revive_kernel_name", "revive_last_error", "revive_status_name"]
@@ -274,6 +275,13 @@ class ReviveLayer:
                                              _ptr(w_sh_down) if use_shared else None,
                                              _ptr(y_shared) if use_shared else None, T, self._stream(stream)))
         return y_perm, y_shared
+
+    def shared_ffn(self, x, w_sh_gate_up, w_sh_down, T: int, out=None, stream=None):
+        if out is None:
+            out = self.empty(T, self.cfg.H)
+        self._check(self.L.revive_shared_ffn(self._ctx, _ptr(x), _ptr(w_sh_gate_up), _ptr(w_sh_down), _ptr(out), T,
+                                             self._stream(stream)))
+        return out
 
     def combine(self, y_perm, dst_row, topk_weight, y_shared, T: int, out=None, stream=None):
         if out is None:

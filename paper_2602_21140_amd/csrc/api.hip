@@ -343,6 +343,16 @@ int revive_expert_ffn(revive_ctx* ctx, const void* x_perm, const int32_t* slot_o
                            static_cast<hipStream_t>(stream));
 }
 
+int revive_shared_ffn(revive_ctx* ctx, const void* x, const void* w_sh_gate_up, const void* w_sh_down, void* y_shared,
+                      int32_t T, revive_stream stream) {
+  int rc = check_call(ctx, "revive_shared_ffn", T, true);
+  if (rc != REVIVE_OK) return rc;
+  if (ctx->cfg.I_shared == 0) return fail(ctx, REVIVE_EINVAL, "revive_shared_ffn: the layer has no shared expert");
+  if (T == 0) return REVIVE_OK;
+  if (!x || !w_sh_gate_up || !w_sh_down || !y_shared) return fail(ctx, REVIVE_EINVAL, "revive_shared_ffn: null argument");
+  return launch_shared_ffn(ctx, x, w_sh_gate_up, w_sh_down, y_shared, T, static_cast<hipStream_t>(stream));
+}
+
 int revive_combine(revive_ctx* ctx, const void* y_perm, const int32_t* dst_row, const float* topk_weight,
                    const void* y_shared, int32_t T, void* out, revive_stream stream) {
   int rc = check_call(ctx, "revive_combine", T, false);

@@ -129,6 +129,8 @@ int launch_dispatch(revive_ctx*, const void* x, const int32_t* topk_phys, int T,
 int launch_expert_ffn(revive_ctx*, const void* x_perm, const int32_t* slot_offsets, const void* const* w_gate_up,
                       const void* const* w_down, void* y_perm, const void* x, const void* w_sh_gate_up,
                       const void* w_sh_down, void* y_shared, int T, hipStream_t);
+int launch_shared_ffn(revive_ctx*, const void* x, const void* w_sh_gate_up, const void* w_sh_down, void* y_shared, int T,
+                      hipStream_t);
 int launch_combine(revive_ctx*, const void* y_perm, const int32_t* dst_row, const float* topk_weight,
                    const void* y_shared, int T, void* out, hipStream_t);
 

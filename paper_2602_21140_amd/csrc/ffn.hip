@@ -129,18 +129,26 @@ int launch_expert_ffn(revive_ctx* ctx, const void* x_perm, const int32_t* slot_o
   MTile* tiles = reinterpret_cast<MTile*>(ctx->d_ws + ctx->ws.off_tiles);
   int32_t* tile_count = reinterpret_cast<int32_t*>(ctx->d_ws + ctx->ws.off_tile_count);
   void* h = ctx->d_ws + ctx->ws.off_h;
-  void* h_shared = ctx->d_ws + ctx->ws.off_h_shared;
   {
     KernelTimer timer(ctx, REVIVE_K_FFN_TILES, stream);
     hipLaunchKernelGGL(ffn_tiles_kernel, dim3(1), dim3(kMaxP), 0, stream, slot_offsets, ctx->P, tile_m, tiles, tile_count);
     REVIVE_HIP(ctx, hipGetLastError());
   }
   const int bound = max_tiles(N, ctx->P, tile_m);
-  constexpr int GU = REVIVE_K_FFN_GATE_UP, DN = REVIVE_K_FFN_DOWN, SGU = REVIVE_K_FFN_SHARED_GATE_UP, SDN = REVIVE_K_FFN_SHARED_DOWN;
+  constexpr int GU = REVIVE_K_FFN_GATE_UP, DN = REVIVE_K_FFN_DOWN;
   int rc = bf16 ? bf16_gemm_pair<GU, DN>(ctx, x_perm, w_gate_up, nullptr, w_down, nullptr, h, y_perm, c.I, tiles, tile_count, 0, bound, stream)
                 : f32_gemm_pair<GU, DN>(ctx, x_perm, w_gate_up, nullptr, w_down, nullptr, h, y_perm, c.I, tiles, tile_count, 0, bound, stream);
   if (rc != REVIVE_OK || !y_shared) return rc;
-  const int dense_tiles = ceil_div(T, tile_m);
+  return launch_shared_ffn(ctx, x, w_sh_gate_up, w_sh_down, y_shared, T, stream);
+}
+
+int launch_shared_ffn(revive_ctx* ctx, const void* x, const void* w_sh_gate_up, const void* w_sh_down, void* y_shared, int T,
+                      hipStream_t stream) {
+  const revive_config& c = ctx->cfg;
+  const bool bf16 = c.dtype == REVIVE_DTYPE_BF16;
+  const int dense_tiles = ceil_div(T, bf16 ? kTileM_bf16 : kTileM_f32);
+  void* h_shared = ctx->d_ws + ctx->ws.off_h_shared;
+  constexpr int SGU = REVIVE_K_FFN_SHARED_GATE_UP, SDN = REVIVE_K_FFN_SHARED_DOWN;
   return bf16 ? bf16_gemm_pair<SGU, SDN>(ctx, x, nullptr, w_sh_gate_up, nullptr, w_sh_down, h_shared, y_shared, c.I_shared, nullptr, nullptr, T, dense_tiles, stream)
               : f32_gemm_pair<SGU, SDN>(ctx, x, nullptr, w_sh_gate_up, nullptr, w_sh_down, h_shared, y_shared, c.I_shared, nullptr, nullptr, T, dense_tiles, stream);
 }

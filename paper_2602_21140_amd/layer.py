@@ -58,35 +58,52 @@ class ResidentLayer:
             src_of=L.empty(T * k, dtype=i32), y_perm=L.empty(T * k, H),
             y_shared=L.empty(T, H) if self.sh_gate_up is not None else None, out=L.empty(T, H))
         self.graph = None
+        self._side = torch.cuda.Stream(device=device)
+        self._ev_fork = torch.cuda.Event()
+        self._ev_join = torch.cuda.Event()
 
     def set_failed(self, failed: Iterable[int], stream=None) -> Dict[str, int]:
         self.failed = synth.failed_mask(self.cfg, failed)
         self.stats = self.layer.update_map(self.failed, stream=stream)
         return self.stats
 
-    def forward(self, logits: Optional[torch.Tensor] = None, shared=True, stream=None) -> Dict[str, Optional[torch.Tensor]]:
-        """route -> dispatch -> expert_ffn -> combine into the preallocated buffers (returned)."""
+    def forward(self, logits: Optional[torch.Tensor] = None, shared=True, stream=None,
+                overlap_shared=True) -> Dict[str, Optional[torch.Tensor]]:
+        """route -> dispatch -> expert_ffn -> combine into the preallocated buffers (returned).
+
+        With overlap_shared the shared expert runs on a side stream next to route/dispatch/routed
+        FFN (fork and join through events, which a stream capture records as graph edges)."""
         c, L, b = self.cfg, self.layer, self.buf
         T = c.T
+        main = torch.cuda.current_stream() if stream is None else stream
+        use_shared = shared and self.sh_gate_up is not None
+        fork = use_shared and overlap_shared
+        if fork:
+            self._ev_fork.record(main)
+            self._side.wait_event(self._ev_fork)
+            L.shared_ffn(self.x, self.sh_gate_up, self.sh_down, T, out=b["y_shared"], stream=self._side)
+            self._ev_join.record(self._side)
         out3 = (b["topk_logical"], b["topk_weight"], b["topk_phys"])
         if logits is None:
-            L.route(self.x, self.w_router_packed, T, logits=b["logits"], out=out3, stream=stream)
+            L.route(self.x, self.w_router_packed, T, logits=b["logits"], out=out3, stream=main)
         else:
             b["logits"].copy_(logits)
-            L.route(None, None, T, logits=b["logits"], logits_given=True, out=out3, stream=stream)
-        L.dispatch(self.x, b["topk_phys"], T, out=(b["x_perm"], b["slot_offsets"], b["dst_row"], b["src_of"]), stream=stream)
-        use_shared = shared and self.sh_gate_up is not None
+            L.route(None, None, T, logits=b["logits"], logits_given=True, out=out3, stream=main)
+        L.dispatch(self.x, b["topk_phys"], T, out=(b["x_perm"], b["slot_offsets"], b["dst_row"], b["src_of"]), stream=main)
+        inline_shared = use_shared and not fork
         L.expert_ffn(b["x_perm"], b["slot_offsets"], T, x=self.x, w_sh_gate_up=self.sh_gate_up, w_sh_down=self.sh_down,
-                     out=(b["y_perm"], b["y_shared"] if use_shared else None), shared=use_shared, stream=stream)
+                     out=(b["y_perm"], b["y_shared"] if inline_shared else None), shared=inline_shared, stream=main)
+        if fork:
+            main.wait_event(self._ev_join)
         L.combine(b["y_perm"], b["dst_row"], b["topk_weight"], b["y_shared"] if use_shared else None, T, out=b["out"],
-                  stream=stream)
+                  stream=main)
         return b
 
-    def capture(self, stream: torch.cuda.Stream):
+    def capture(self, stream: torch.cuda.Stream, overlap_shared=True):
         """Record one forward on `stream` into a graph (instantiated once)."""
         self.layer.graph_begin(stream)
         try:
-            self.forward(stream=stream)
+            self.forward(stream=stream, overlap_shared=overlap_shared)
         finally:
             self.graph = self.layer.graph_end(stream)
         return self.graph
