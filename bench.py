@@ -193,7 +193,7 @@ def main():
                                + f", {cfg.n_ranks} simulated ranks x {cfg.slots_per_rank} slots, failed ranks "
                                f"{list(cfg.failed_ranks)}",
                    "map": g.stats, "execution": "one captured graph replayed per step" + (", shared expert on a side stream" if ov else "")},
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel<SwiGLU> (ffn_gate_up)" if cfg.dtype == "bf16" else "gemm_f32_kernel<SwiGLU>",
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_dma_kernel<256,256,2,4,SwiGLU> (ffn_gate_up)" if cfg.dtype == "bf16" else "gemm_f32_kernel<SwiGLU> (ffn_gate_up)",
                      "achieved": dom_tflops, "peak": peak, "unit": "TFLOP/s", "frac": dom_tflops / peak,
                      "avg_launch_us": avg_us[dom], "flops_per_launch": work["gate_up_flops"], "traffic": None},
         "stages": stages,
