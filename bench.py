@@ -159,7 +159,10 @@ def main():
 
     avg_us = {n: (1e3 * ms / c if c else None) for n, (ms, c) in times.items()}
     dom = "ffn_gate_up"
-    dom_tflops = work["gate_up_flops"] / (avg_us[dom] * 1e-6) / 1e12
+    # with a shared expert the library serves routed and shared gate/up projections in one launch
+    merged = cfg.I_shared > 0 and avg_us["ffn_shared_gate_up"] is None
+    dom_flops = work["gate_up_flops"] + (work["shared_gate_up_flops"] if merged else 0)
+    dom_tflops = dom_flops / (avg_us[dom] * 1e-6) / 1e12
     peak = MFMA_PEAK_TFLOPS[cfg.dtype]
 
     def gbs(nbytes, names):
@@ -195,7 +198,9 @@ def main():
                    "map": g.stats, "execution": "one captured graph replayed per step" + (", shared expert on a side stream" if ov else "")},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_dma_kernel<256,256,2,4,SwiGLU> (ffn_gate_up)" if cfg.dtype == "bf16" else "gemm_f32_kernel<SwiGLU> (ffn_gate_up)",
                      "achieved": dom_tflops, "peak": peak, "unit": "TFLOP/s", "frac": dom_tflops / peak,
-                     "avg_launch_us": avg_us[dom], "flops_per_launch": work["gate_up_flops"], "traffic": None},
+                     "avg_launch_us": avg_us[dom], "flops_per_launch": dom_flops,
+                     "launch_covers": "routed experts + shared expert gate/up projections" if merged else "routed experts gate/up projection",
+                     "traffic": None},
         "stages": stages,
         "remap": {"update_map_host_ms": host_ms, "update_to_first_step_done_ms": first_ms,
                   "minus_steady_step_ms": first_ms - ms_per_step, "routes_avoid_failed_ranks": all(r[2] for r in remap),

@@ -58,35 +58,73 @@ __global__ __launch_bounds__(kMaxP) void ffn_tiles_kernel(const int32_t* __restr
 }
 
 // Tile shapes of the bf16 GEMMs: 256 x 256 outputs per workgroup of 8 wavefronts (2 x 4), K in
-// steps of 32 through a four-stage ring of asynchronous global->LDS copies.
+// steps of 32 through a four-stage ring of asynchronous global->LDS copies.  Problems too small
+// to give every CU a 256 x 256 tile use 256 x 128 tiles on 4 wavefronts (two workgroups per CU).
 constexpr int kBM = kTileM_bf16, kBN = 256, kWM = 2, kWN = 4;
 
-template <int K_GATE_UP, int K_DOWN>
-int bf16_gemm_pair(revive_ctx* ctx, const void* A, const void* const* gu_tab, const void* gu_one, const void* const* dn_tab,
-                   const void* dn_one, void* h, void* y, int I, const MTile* tiles, const int32_t* tile_count, int M,
-                   int max_m_tiles, hipStream_t stream) {
-  const int H = ctx->cfg.H;
+struct Bf16Ffn {  // one SwiGLU FFN: rows of A -> h -> y
+  const void* A;
+  const void* const* gu_tab; const void* gu_one;
+  const void* const* dn_tab; const void* dn_one;
+  void* h; void* y;
+  int I;
+  const MTile* tiles; const int32_t* tile_count; int M;
+  int max_m_tiles;
+};
+
+GemmArgs gate_up_args(const revive_ctx* ctx, const Bf16Ffn& f, int bn_out) {
   GemmArgs a{};
-  a.A = A; a.lda = H;
-  a.B_tab = gu_tab; a.B_one = gu_one; a.ldb = H;
-  a.C = h; a.ldc = I;
-  a.n_out = I; a.K = H;
-  a.tiles = tiles; a.tile_count = tile_count; a.M = M;
-  a.n_col_tiles = ceil_div(I, kBN / 2);
+  a.A = f.A; a.lda = ctx->cfg.H;
+  a.B_tab = f.gu_tab; a.B_one = f.gu_one; a.ldb = ctx->cfg.H;
+  a.C = f.h; a.ldc = f.I;
+  a.n_out = f.I; a.K = ctx->cfg.H;
+  a.tiles = f.tiles; a.tile_count = f.tile_count; a.M = f.M;
+  a.n_col_tiles = ceil_div(f.I, bn_out);
+  return a;
+}
+
+GemmArgs down_args(const revive_ctx* ctx, const Bf16Ffn& f, int bn_out) {
+  GemmArgs d{};
+  d.A = f.h; d.lda = f.I;
+  d.B_tab = f.dn_tab; d.B_one = f.dn_one; d.ldb = f.I;
+  d.C = f.y; d.ldc = ctx->cfg.H;
+  d.n_out = ctx->cfg.H; d.K = f.I;
+  d.tiles = f.tiles; d.tile_count = f.tile_count; d.M = f.M;
+  d.n_col_tiles = ceil_div(ctx->cfg.H, bn_out);
+  return d;
+}
+
+// Runs one FFN, or two in the same pair of launches (their tiles share the grid, which shortens
+// the partially filled last round of workgroups).  K_GATE_UP / K_DOWN name the launches.
+template <int K_GATE_UP, int K_DOWN>
+int bf16_ffn(revive_ctx* ctx, const Bf16Ffn& f0, const Bf16Ffn* f1, hipStream_t stream) {
+  const int H = ctx->cfg.H;
+  const int64_t tiles_big_down = static_cast<int64_t>(f0.max_m_tiles) * ceil_div(H, kBN) +
+                                 (f1 ? static_cast<int64_t>(f1->max_m_tiles) * ceil_div(H, kBN) : 0);
+  const bool small = !f1 && f0.tiles == nullptr && tiles_big_down < 2 * 256;  // dense and under two tiles per CU
   {
     KernelTimer timer(ctx, K_GATE_UP, stream);
-    int rc = launch_gemm_bf16<kBM, kBN, kWM, kWN, EPI_SWIGLU, K_GATE_UP, true>(ctx, a, max_m_tiles, stream);
+    int rc;
+    if (small) {
+      GemmArgs a0 = gate_up_args(ctx, f0, 64);
+      rc = launch_gemm_bf16_dma<kBM, 128, 2, 2, EPI_SWIGLU, K_GATE_UP>(ctx, a0, f0.max_m_tiles, nullptr, 0, stream);
+    } else {
+      GemmArgs a0 = gate_up_args(ctx, f0, kBN / 2), a1{};
+      if (f1) a1 = gate_up_args(ctx, *f1, kBN / 2);
+      rc = launch_gemm_bf16_dma<kBM, kBN, kWM, kWN, EPI_SWIGLU, K_GATE_UP>(ctx, a0, f0.max_m_tiles, f1 ? &a1 : nullptr,
+                                                                           f1 ? f1->max_m_tiles : 0, stream);
+    }
     if (rc != REVIVE_OK) return rc;
   }
-  GemmArgs d{};
-  d.A = h; d.lda = I;
-  d.B_tab = dn_tab; d.B_one = dn_one; d.ldb = I;
-  d.C = y; d.ldc = H;
-  d.n_out = H; d.K = I;
-  d.tiles = tiles; d.tile_count = tile_count; d.M = M;
-  d.n_col_tiles = ceil_div(H, kBN);
   KernelTimer timer(ctx, K_DOWN, stream);
-  return launch_gemm_bf16<kBM, kBN, kWM, kWN, EPI_BF16, K_DOWN, true>(ctx, d, max_m_tiles, stream);
+  if (small) {
+    GemmArgs d0 = down_args(ctx, f0, 128);
+    return launch_gemm_bf16_dma<kBM, 128, 2, 2, EPI_BF16, K_DOWN>(ctx, d0, f0.max_m_tiles, nullptr, 0, stream);
+  }
+  GemmArgs d0 = down_args(ctx, f0, kBN), d1{};
+  if (f1) d1 = down_args(ctx, *f1, kBN);
+  return launch_gemm_bf16_dma<kBM, kBN, kWM, kWN, EPI_BF16, K_DOWN>(ctx, d0, f0.max_m_tiles, f1 ? &d1 : nullptr,
+                                                                    f1 ? f1->max_m_tiles : 0, stream);
 }
 
 template <int K_GATE_UP, int K_DOWN>
@@ -136,8 +174,15 @@ int launch_expert_ffn(revive_ctx* ctx, const void* x_perm, const int32_t* slot_o
   }
   const int bound = max_tiles(N, ctx->P, tile_m);
   constexpr int GU = REVIVE_K_FFN_GATE_UP, DN = REVIVE_K_FFN_DOWN;
-  int rc = bf16 ? bf16_gemm_pair<GU, DN>(ctx, x_perm, w_gate_up, nullptr, w_down, nullptr, h, y_perm, c.I, tiles, tile_count, 0, bound, stream)
-                : f32_gemm_pair<GU, DN>(ctx, x_perm, w_gate_up, nullptr, w_down, nullptr, h, y_perm, c.I, tiles, tile_count, 0, bound, stream);
+  if (bf16) {
+    Bf16Ffn routed{x_perm, w_gate_up, nullptr, w_down, nullptr, h, y_perm, c.I, tiles, tile_count, 0, bound};
+    if (!y_shared) return bf16_ffn<GU, DN>(ctx, routed, nullptr, stream);
+    // routed and shared experts in the same two launches
+    Bf16Ffn shared{x, nullptr, w_sh_gate_up, nullptr, w_sh_down, ctx->d_ws + ctx->ws.off_h_shared, y_shared, c.I_shared,
+                   nullptr, nullptr, T, ceil_div(T, tile_m)};
+    return bf16_ffn<GU, DN>(ctx, routed, &shared, stream);
+  }
+  int rc = f32_gemm_pair<GU, DN>(ctx, x_perm, w_gate_up, nullptr, w_down, nullptr, h, y_perm, c.I, tiles, tile_count, 0, bound, stream);
   if (rc != REVIVE_OK || !y_shared) return rc;
   return launch_shared_ffn(ctx, x, w_sh_gate_up, w_sh_down, y_shared, T, stream);
 }
@@ -149,8 +194,11 @@ int launch_shared_ffn(revive_ctx* ctx, const void* x, const void* w_sh_gate_up, 
   const int dense_tiles = ceil_div(T, bf16 ? kTileM_bf16 : kTileM_f32);
   void* h_shared = ctx->d_ws + ctx->ws.off_h_shared;
   constexpr int SGU = REVIVE_K_FFN_SHARED_GATE_UP, SDN = REVIVE_K_FFN_SHARED_DOWN;
-  return bf16 ? bf16_gemm_pair<SGU, SDN>(ctx, x, nullptr, w_sh_gate_up, nullptr, w_sh_down, h_shared, y_shared, c.I_shared, nullptr, nullptr, T, dense_tiles, stream)
-              : f32_gemm_pair<SGU, SDN>(ctx, x, nullptr, w_sh_gate_up, nullptr, w_sh_down, h_shared, y_shared, c.I_shared, nullptr, nullptr, T, dense_tiles, stream);
+  if (bf16) {
+    Bf16Ffn shared{x, nullptr, w_sh_gate_up, nullptr, w_sh_down, h_shared, y_shared, c.I_shared, nullptr, nullptr, T, dense_tiles};
+    return bf16_ffn<SGU, SDN>(ctx, shared, nullptr, stream);
+  }
+  return f32_gemm_pair<SGU, SDN>(ctx, x, nullptr, w_sh_gate_up, nullptr, w_sh_down, h_shared, y_shared, c.I_shared, nullptr, nullptr, T, dense_tiles, stream);
 }
 
 }  // namespace revive

@@ -58,6 +58,13 @@ struct GemmArgs {
   int n_col_tiles;
 };
 
+// Up to two independent problems served by one launch (e.g. the routed experts' grouped GEMM and
+// the shared expert's dense GEMM): their tiles are numbered one after the other.
+struct GemmArgs2 {
+  GemmArgs p0, p1;
+  int two;  // 0: only p0 is valid
+};
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
 // Round-to-nearest-even fp32 -> bf16 bits (finite inputs).
@@ -298,13 +305,13 @@ __host__ __device__ constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 0xF) |
 
 __device__ __forceinline__ int swz32(int row) { return (row >> 2) & 3; }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int KID>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(GemmArgs g) {
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int KID, int STAGES = 4>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(GemmArgs2 a2) {
   constexpr int NT = 64 * WAVES_M * WAVES_N, NW = WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int BN_OUT = EPI == EPI_SWIGLU ? BN / 2 : BN;
-  constexpr int STAGES = 4;
+  constexpr int D = STAGES - 1;  // copies run D K-steps ahead of the MFMAs
   constexpr int STAGE = (BM + BN) * 64;       // bytes
   constexpr int CP_A = BM / 16 / NW, CP_B = BN / 16 / NW;  // copy instructions per wavefront and stage
   constexpr int CP = CP_A + CP_B;
@@ -315,13 +322,28 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   typedef __attribute__((address_space(3))) void* lptr;
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  auto stage_of = [](int kt) { return (STAGES & (STAGES - 1)) == 0 ? (kt & (STAGES - 1)) : kt % STAGES; };
 
-  const int n_m_tiles = g.tiles ? *g.tile_count : (g.M + BM - 1) / BM;
-  const int total = n_m_tiles * g.n_col_tiles;
-  const int per_xcd = (total + 7) >> 3;
-  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-  const int logical = xcd * per_xcd + local;
-  if (local >= per_xcd || logical >= total) return;
+  // Tile -> workgroup map.  Workgroup i runs on XCD i % 8; each XCD takes a contiguous eighth of
+  // every problem's tiles (neighbouring tiles share activations / weights in that XCD's L2), and
+  // works through the problem with the longer K first so that the cheap tiles fill the last round.
+  const int t0 = (a2.p0.tiles ? *a2.p0.tile_count : (a2.p0.M + BM - 1) / BM) * a2.p0.n_col_tiles;
+  const int t1 = a2.two ? (a2.p1.tiles ? *a2.p1.tile_count : (a2.p1.M + BM - 1) / BM) * a2.p1.n_col_tiles : 0;
+  const int px0 = (t0 + 7) >> 3, px1 = (t1 + 7) >> 3;
+  const int xcd = blockIdx.x & 7;
+  int local = blockIdx.x >> 3;
+  const bool p1_first = a2.two && a2.p1.K > a2.p0.K;
+  bool second;  // uniform: this workgroup serves the second problem
+  if (p1_first) {
+    second = local < px1;
+    if (!second) local -= px1;
+  } else {
+    second = local >= px0;
+    if (second) local -= px0;
+  }
+  const int logical = xcd * (second ? px1 : px0) + local;
+  if (local >= (second ? px1 : px0) || logical >= (second ? t1 : t0)) return;
+  const GemmArgs g = second ? a2.p1 : a2.p0;
   const int m_idx = logical / g.n_col_tiles;
   const int n_idx = logical - m_idx * g.n_col_tiles;
 
@@ -376,7 +398,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   // copies are invisible to that bookkeeping and are waited for explicitly before each barrier.
   const uint32_t smem_lds = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lptr)smem));
   auto issue_copy = [&](int kt) {
-    const uint32_t stage = smem_lds + (kt & (STAGES - 1)) * STAGE;
+    const uint32_t stage = smem_lds + stage_of(kt) * STAGE;
     const int64_t koff = static_cast<int64_t>(kt) * 64;  // 32 bf16
 #pragma unroll
     for (int i = 0; i < CP; ++i) {
@@ -447,9 +469,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
     auto step = [&](int kt, auto copy_tag, auto vm_tag, auto last_tag) {
       constexpr bool COPY = decltype(copy_tag)::value, LAST = decltype(last_tag)::value;
       constexpr int VM = decltype(vm_tag)::value;
-      const unsigned char* cur = smem + (kt & (STAGES - 1)) * STAGE;
+      const unsigned char* cur = smem + stage_of(kt) * STAGE;
       // stage (kt+3)%4 held step kt-1, which every wavefront finished reading before the last barrier
-      if (COPY) issue_copy(kt + 3);
+      if (COPY) issue_copy(kt + D);
       load_frags(cur, 1, af1, bf1);
       __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the MFMAs they overlap with
       mfma_step(af0, bf0);
@@ -461,7 +483,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(VM));
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        load_frags(smem + ((kt + 1) & (STAGES - 1)) * STAGE, 0, af0, bf0);
+        load_frags(smem + stage_of(kt + 1) * STAGE, 0, af0, bf0);
         __builtin_amdgcn_sched_barrier(0);
       }
       mfma_step(af1, bf1);
@@ -469,19 +491,62 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
     };
     using T = std::true_type;
     using F = std::false_type;
-    load_frags(smem, 0, af0, bf0);
-    int kt = 0;
-    for (; kt + 3 < KT; ++kt) step(kt, T{}, std::integral_constant<int, 2 * CP>{}, F{});
-    if (kt + 2 < KT) { step(kt, F{}, std::integral_constant<int, CP>{}, F{}); ++kt; }
-    if (kt + 1 < KT) { step(kt, F{}, std::integral_constant<int, 0>{}, F{}); ++kt; }
-    step(kt, F{}, std::integral_constant<int, 0>{}, T{});
+    // Skewed schedule.  Both wavefronts of a SIMD (w and w + NW/2) would otherwise leave the
+    // barrier in lockstep and do their non-MFMA work (copy issue, address arithmetic) at the same
+    // time, leaving the matrix pipe idle.  The late group issues its copy right after the barrier
+    // (one step further ahead) instead of after the second half-step's MFMAs, so one group's
+    // overhead always runs under the other group's MFMAs.
+    auto step_late = [&](int kt, auto copy_tag, auto vm_tag, auto last_tag) {
+      constexpr bool COPY = decltype(copy_tag)::value, LAST = decltype(last_tag)::value;
+      constexpr int VM = decltype(vm_tag)::value;
+      const unsigned char* cur = smem + stage_of(kt) * STAGE;
+      load_frags(cur, 1, af1, bf1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_step(af0, bf0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (!LAST) {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(VM));
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (COPY) issue_copy(kt + D + 1);  // into this step's own stage: all its reads ended before the barrier
+        load_frags(smem + stage_of(kt + 1) * STAGE, 0, af0, bf0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      mfma_step(af1, bf1);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    // Tail: with j copies-ahead steps left, (j - 1) * CP copies may stay pending at the barrier.
+    auto tail = [&](auto& fn, int& kt) {
+      if (D >= 3 && kt + 3 < KT) { fn(kt, F{}, std::integral_constant<int, 2 * CP>{}, F{}); ++kt; }
+      if (D >= 2 && kt + 2 < KT) { fn(kt, F{}, std::integral_constant<int, CP>{}, F{}); ++kt; }
+      if (kt + 1 < KT) { fn(kt, F{}, std::integral_constant<int, 0>{}, F{}); ++kt; }
+      fn(kt, F{}, std::integral_constant<int, 0>{}, T{});
+    };
+    constexpr int VM_STEADY = (D - 1) * CP;
+    if (wave < NW / 2) {
+      load_frags(smem, 0, af0, bf0);
+      int kt = 0;
+      for (; kt + D < KT; ++kt) step(kt, T{}, std::integral_constant<int, VM_STEADY>{}, F{});
+      // here kt + D >= KT: the copies of every remaining step are already issued
+      if (D >= 3 && kt + 2 < KT) { step(kt, F{}, std::integral_constant<int, CP>{}, F{}); ++kt; }
+      if (kt + 1 < KT) { step(kt, F{}, std::integral_constant<int, 0>{}, F{}); ++kt; }
+      step(kt, F{}, std::integral_constant<int, 0>{}, T{});
+    } else {
+      if (KT > D) issue_copy(D);
+      load_frags(smem, 0, af0, bf0);
+      int kt = 0;
+      for (; kt + D + 1 < KT; ++kt) step_late(kt, T{}, std::integral_constant<int, VM_STEADY>{}, F{});
+      tail(step_late, kt);
+    }
   };
 
+  // prologue: copies of the first D steps, then publish step 0
   issue_copy(0);
   if (KT > 1) issue_copy(1);
-  if (KT > 2) issue_copy(2);
+  if (D >= 3 && KT > 2) issue_copy(2);
   asm volatile("" ::: "memory");
-  if (KT > 2) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * CP));
+  if (D >= 3 && KT > 2) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * CP));
   else if (KT > 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(CP));
   else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
   __builtin_amdgcn_s_barrier();
@@ -538,14 +603,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   }
 }
 
-// Launch helper: grid covers `max_m_tiles` row-tiles (an upper bound; surplus workgroups exit).
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int KID, bool DMA = false>
+// Launch helpers: grids cover `max_m_tiles` row-tiles per problem (upper bounds; surplus
+// workgroups exit at once).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int KID>
 int launch_gemm_bf16(revive_ctx* ctx, const GemmArgs& args, int max_m_tiles, hipStream_t stream) {
   constexpr int NT = 64 * WAVES_M * WAVES_N;
-  constexpr size_t lds = DMA ? 4 * (BM + BN) * 64 : 2 * (BM + BN) * 128;
-  void (*kern)(GemmArgs);
-  if constexpr (DMA) kern = gemm_bf16_dma_kernel<BM, BN, WAVES_M, WAVES_N, EPI, KID>;
-  else kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, EPI, KID>;
+  constexpr size_t lds = 2 * (BM + BN) * 128;
+  auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, EPI, KID>;
   static bool configured = false;  // per instantiation
   if (!configured) {
     REVIVE_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -557,6 +621,30 @@ int launch_gemm_bf16(revive_ctx* ctx, const GemmArgs& args, int max_m_tiles, hip
   const int grid = static_cast<int>((total + 7) / 8 * 8);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, stream, args);
   return check_hip(ctx, hipGetLastError(), "gemm_bf16 launch");
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int KID, int STAGES = 4>
+int launch_gemm_bf16_dma(revive_ctx* ctx, const GemmArgs& p0, int max_m_tiles0, const GemmArgs* p1, int max_m_tiles1,
+                         hipStream_t stream) {
+  constexpr int NT = 64 * WAVES_M * WAVES_N;
+  constexpr size_t lds = STAGES * (BM + BN) * 64;
+  auto kern = gemm_bf16_dma_kernel<BM, BN, WAVES_M, WAVES_N, EPI, KID, STAGES>;
+  static bool configured = false;  // per instantiation
+  if (!configured) {
+    REVIVE_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        static_cast<int>(lds)));
+    configured = true;
+  }
+  GemmArgs2 a{};
+  a.p0 = p0;
+  a.two = p1 != nullptr;
+  if (p1) a.p1 = *p1;
+  const int64_t per_xcd = (static_cast<int64_t>(max_m_tiles0) * p0.n_col_tiles + 7) / 8 +
+                          (p1 ? (static_cast<int64_t>(max_m_tiles1) * p1->n_col_tiles + 7) / 8 : 0);
+  if (per_xcd <= 0) return REVIVE_OK;
+  const int grid = static_cast<int>(per_xcd * 8);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, stream, a);
+  return check_hip(ctx, hipGetLastError(), "gemm_bf16_dma launch");
 }
 
 }  // namespace revive
