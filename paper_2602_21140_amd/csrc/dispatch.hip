@@ -47,7 +47,19 @@ __global__ __launch_bounds__(kMaxP) void dispatch_scan_kernel(int32_t* __restric
   const int p = threadIdx.x;
   int run = 0;
   if (p < P) {
-    for (int b = 0; b < n_chunks; ++b) {
+    // eight independent loads in flight per thread, then the dependent running sum
+    int b = 0;
+    for (; b + 8 <= n_chunks; b += 8) {
+      int v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = block_hist[static_cast<int64_t>(b + j) * P + p];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        block_hist[static_cast<int64_t>(b + j) * P + p] = run;
+        run += v[j];
+      }
+    }
+    for (; b < n_chunks; ++b) {
       const int64_t o = static_cast<int64_t>(b) * P + p;
       const int v = block_hist[o];
       block_hist[o] = run;

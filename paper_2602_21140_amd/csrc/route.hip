@@ -11,8 +11,6 @@ namespace revive {
 
 namespace {
 
-constexpr int kVals = kMaxE / 64;  // logits held per lane
-
 // Ordering of candidates: larger key first, equal keys by lower expert id.
 __device__ __forceinline__ bool better(float ka, int ea, float kb, int eb) { return ka > kb || (ka == kb && ea < eb); }
 
@@ -27,21 +25,23 @@ struct RouteParams {
   float route_scale;
 };
 
-// One wavefront per token.  Lane l holds the logits of experts l, l+64, l+128, ...; a masked or
-// excluded expert's key is -inf.  Expert order is decided on the fp32 logits themselves (softmax
-// and sigmoid are increasing, so this is the order of the scores); group scores, which add two
-// scores, and the output weights are evaluated in fp64.
+// One wavefront per token.  Lane l holds the logits of experts l, l+64, l+128, ... (VALS of them);
+// a masked or excluded expert's key is -inf.  Expert order is decided on the fp32 logits
+// themselves (softmax and sigmoid are increasing, so this is the order of the scores); group
+// scores, which add two scores, and the output weights are evaluated in fp64.
+// GROUPED variants hold the group scores in registers (n_group <= 8 or <= 32).
+template <int VALS, int MAXG>
 __global__ __launch_bounds__(256) void route_topk_kernel(RouteParams p) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= p.T) return;  // whole wavefront leaves together
   const float NEG = -__builtin_inff();
 
-  float key[kVals];
+  float key[VALS];
   const float* row = p.logits + static_cast<int64_t>(t) * p.E;
   float vmax = NEG;  // largest logit of the row, masked or not: common shift of the exponentials
 #pragma unroll
-  for (int i = 0; i < kVals; ++i) {
+  for (int i = 0; i < VALS; ++i) {
     const int e = lane + 64 * i;
     float z = NEG;
     if (e < p.E) {
@@ -60,16 +60,17 @@ __global__ __launch_bounds__(256) void route_topk_kernel(RouteParams p) {
     return p.score_fn == REVIVE_SCORE_SIGMOID ? 1.0 / (1.0 + exp(-zd)) : exp(zd - shift);
   };
 
-  if (p.n_group > 1) {
+  if (MAXG > 1) {
     // Group score = sum of the two best live scores of the group (one if only one is live, -inf
-    // if none).  Computed by every lane redundantly after a wave-wide top-2 per group.
+    // if none).  A wave-wide top-2 per group finds the two logits; lane g then evaluates group
+    // g's score in fp64 and every lane ranks it against the others through shuffles.
     const int gsz = p.E / p.n_group;
-    double gscore[32];
+    float top1 = NEG, top2 = NEG;  // lane g keeps group g's two best keys
 #pragma unroll 1
     for (int g = 0; g < p.n_group; ++g) {
-      float m1 = NEG, m2 = NEG;  // the lane's two best keys inside group g
+      float m1 = NEG, m2 = NEG;
 #pragma unroll
-      for (int i = 0; i < kVals; ++i) {
+      for (int i = 0; i < VALS; ++i) {
         const int e = lane + 64 * i;
         const float z = (e < p.E && e / gsz == g) ? key[i] : NEG;
         if (z > m1) { m2 = m1; m1 = z; } else if (z > m2) { m2 = z; }
@@ -82,25 +83,25 @@ __global__ __launch_bounds__(256) void route_topk_kernel(RouteParams p) {
         m1 = hi;
         m2 = lo;
       }
-      double s = -__builtin_inf();
-      if (m1 > NEG) {
-        s = score64(m1);
-        if (m2 > NEG) s += score64(m2);
-      }
-      gscore[g] = s;
+      if (lane == g) { top1 = m1; top2 = m2; }
     }
-    // Keep the topk_group best groups, ties to the lower group id; drop the experts of the rest.
-#pragma unroll 1
-    for (int g = 0; g < p.n_group; ++g) {
-      int rank = 0;
-      for (int h = 0; h < p.n_group; ++h) rank += (gscore[h] > gscore[g]) || (gscore[h] == gscore[g] && h < g);
-      if (rank >= p.topk_group) {
+    double gs = -__builtin_inf();
+    if (lane < p.n_group && top1 > NEG) {
+      gs = score64(top1);
+      if (top2 > NEG) gs += score64(top2);
+    }
+    // rank of my group among all groups (better score first, ties to the lower group id)
+    int rank = 0;
 #pragma unroll
-        for (int i = 0; i < kVals; ++i) {
-          const int e = lane + 64 * i;
-          if (e < p.E && e / gsz == g) key[i] = NEG;
-        }
-      }
+    for (int h = 0; h < MAXG; ++h) {
+      const double o = __shfl(gs, h);
+      if (h < p.n_group) rank += (o > gs) || (o == gs && h < lane);
+    }
+    const unsigned long long kept = __ballot(lane < p.n_group && rank < p.topk_group);
+#pragma unroll
+    for (int i = 0; i < VALS; ++i) {
+      const int e = lane + 64 * i;
+      if (e < p.E && !((kept >> (e / gsz)) & 1ull)) key[i] = NEG;  // expert of a dropped group
     }
   }
 
@@ -111,7 +112,7 @@ __global__ __launch_bounds__(256) void route_topk_kernel(RouteParams p) {
     float bk = NEG;
     int be = 0x7fffffff;
 #pragma unroll
-    for (int i = 0; i < kVals; ++i) {
+    for (int i = 0; i < VALS; ++i) {
       const int e = lane + 64 * i;
       if (e < p.E && better(key[i], e, bk, be)) { bk = key[i]; be = e; }
     }
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(256) void route_topk_kernel(RouteParams p) {
     }
     if ((be & 63) == lane) {
 #pragma unroll
-      for (int i = 0; i < kVals; ++i)
+      for (int i = 0; i < VALS; ++i)
         if (i == (be >> 6)) key[i] = NEG;
     }
     if (lane == j) { my_e = be; my_z = bk; }
@@ -184,7 +185,20 @@ int launch_route_topk(revive_ctx* ctx, const float* logits, int T, int32_t* topk
   p.score_fn = c.score_fn; p.n_group = c.n_group; p.topk_group = c.topk_group;
   p.route_scale = c.route_scale;
   KernelTimer timer(ctx, REVIVE_K_ROUTE_TOPK, stream);
-  hipLaunchKernelGGL(route_topk_kernel, dim3(ceil_div(T, 4)), dim3(256), 0, stream, p);
+  const dim3 grid(ceil_div(T, 4)), block(256);
+  const int vals = ceil_div(c.E, 64);
+#define REVIVE_ROUTE_LAUNCH(V)                                                                               \
+  do {                                                                                                       \
+    if (c.n_group <= 1) hipLaunchKernelGGL((route_topk_kernel<V, 1>), grid, block, 0, stream, p);            \
+    else if (c.n_group <= 8) hipLaunchKernelGGL((route_topk_kernel<V, 8>), grid, block, 0, stream, p);       \
+    else hipLaunchKernelGGL((route_topk_kernel<V, 32>), grid, block, 0, stream, p);                          \
+  } while (0)
+  if (vals <= 1) REVIVE_ROUTE_LAUNCH(1);
+  else if (vals <= 2) REVIVE_ROUTE_LAUNCH(2);
+  else if (vals <= 4) REVIVE_ROUTE_LAUNCH(4);
+  else if (vals <= 6) REVIVE_ROUTE_LAUNCH(6);
+  else REVIVE_ROUTE_LAUNCH(8);
+#undef REVIVE_ROUTE_LAUNCH
   return check_hip(ctx, hipGetLastError(), "route_topk launch");
 }
 
