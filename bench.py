@@ -90,6 +90,9 @@ def main():
     ap.add_argument("--overlap-shared", action="store_true",
                     help="run the shared expert on a side stream next to route/dispatch (off by default so that "
                          "every kernel of the step runs alone and its timing is its own)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain device copy of 1 GiB (read 1 GiB, write 1 GiB) so that hardware "
+                         "counters collected over this command can be scaled by a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (expert-parallel ranks are simulated as rank segments "
@@ -156,6 +159,13 @@ def main():
         g.set_failed(cfg.failed_ranks, stream=stream)
         stream.synchronize()
         same_exec = L.graph_exec_id(g.graph) == exec_id
+
+    if args.calibration_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     avg_us = {n: (1e3 * ms / c if c else None) for n, (ms, c) in times.items()}
     dom = "ffn_gate_up"

@@ -29,7 +29,7 @@ struct MTile {
   int32_t group;
   int32_t row_begin;
   int32_t row_end;
-  int32_t pad;
+  int32_t pad;  // (row-tiles of the group << 16) | position of this tile inside its group
 };
 
 // Device-resident map, one contiguous blob at a fixed address so that one copy updates it.

@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kMaxP) void ffn_tiles_kernel(const int32_t* __restr
     t.group = p;
     t.row_begin = first + i * tile_m;
     t.row_end = min(end, first + (i + 1) * tile_m);
-    t.pad = 0;
+    t.pad = (mine << 16) | i;  // row-tiles of this slot, and this one's position among them
     tiles[base + i] = t;
   }
 }

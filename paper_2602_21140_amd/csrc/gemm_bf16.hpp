@@ -344,12 +344,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   const int logical = xcd * (second ? px1 : px0) + local;
   if (local >= (second ? px1 : px0) || logical >= (second ? t1 : t0)) return;
   const GemmArgs g = second ? a2.p1 : a2.p0;
-  const int m_idx = logical / g.n_col_tiles;
-  const int n_idx = logical - m_idx * g.n_col_tiles;
+  int m_idx = logical / g.n_col_tiles;
+  int n_idx = logical - m_idx * g.n_col_tiles;
 
   int group = 0, row_begin, row_end;
   if (g.tiles) {
-    const MTile t = g.tiles[m_idx];
+    // Inside one group's block of tiles the column index runs slowest: the row-tiles of a slot
+    // that use the same weight columns are neighbours in launch order and meet in L2.
+    MTile t = g.tiles[m_idx];
+    const int in_group = t.pad >> 16, first = m_idx - (t.pad & 0xFFFF);
+    if (in_group > 1) {
+      const int r = logical - first * g.n_col_tiles;
+      n_idx = r / in_group;
+      m_idx = first + (r - n_idx * in_group);
+      t = g.tiles[m_idx];
+    }
     group = t.group;
     row_begin = t.row_begin;
     row_end = t.row_end;
