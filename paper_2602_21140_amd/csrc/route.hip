@@ -145,11 +145,134 @@ __global__ __launch_bounds__(256) void route_topk_kernel(RouteParams p) {
   }
 }
 
+// Router logits for a small router (E <= 128) without LDS staging.  A workgroup of KS wavefronts
+// owns 32 tokens and all E experts; wavefront w multiplies the w-th slice of the hidden dimension
+// with operands loaded straight from global memory in MFMA fragment order, and the KS partial
+// sums are added in wavefront order through LDS (a fixed order: the result is deterministic).
+// Per 64-wide K block a lane reads 64 contiguous bytes of its token row (lanes l and l+32 cover
+// one 128-byte line), so x is streamed once in full lines; the router matrix stays in L2.
+// Up to three K blocks are in flight per wavefront.
+template <int NTN, int KS>
+__global__ __launch_bounds__(64 * KS) void router_direct_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
+                                                                float* __restrict__ logits, int T, int E, int H) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  float* part = reinterpret_cast<float*>(smem);  // [KS-1][NTN][16][64]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 31, half = lane >> 5;
+  const int row0 = blockIdx.x * 32;
+  const int kq = H / KS;  // K range of one wavefront, a multiple of 64
+  const int64_t koff = static_cast<int64_t>(wave) * kq + half * 32;
+  const unsigned char* a_ptr = reinterpret_cast<const unsigned char*>(x + static_cast<int64_t>(min(row0 + r, T - 1)) * H + koff);
+  const unsigned char* b_ptr[NTN];
+#pragma unroll
+  for (int tn = 0; tn < NTN; ++tn)
+    b_ptr[tn] = reinterpret_cast<const unsigned char*>(w + static_cast<int64_t>(min(tn * 32 + r, E - 1)) * H + koff);
+
+  f32x16 acc[NTN];
+#pragma unroll
+  for (int tn = 0; tn < NTN; ++tn)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[tn][i] = 0.f;
+
+  struct Frags { u32x4 a[4]; u32x4 b[NTN][4]; };
+  auto load = [&](int blk, Frags& f) {
+    const int64_t o = static_cast<int64_t>(blk) * 128;  // 64 bf16
+#pragma unroll
+    for (int j = 0; j < 4; ++j) f.a[j] = load_global_16B(a_ptr + o + j * 16);
+#pragma unroll
+    for (int tn = 0; tn < NTN; ++tn)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) f.b[tn][j] = load_global_16B(b_ptr[tn] + o + j * 16);
+  };
+  auto mac = [&](const Frags& f) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int tn = 0; tn < NTN; ++tn)
+        acc[tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.b[tn][j]), __builtin_bit_cast(bf16x8, f.a[j]),
+                                                          acc[tn], 0, 0, 0);
+  };
+  const int n = kq >> 6;
+  Frags f0, f1, f2;
+  load(0, f0);
+  if (n > 1) load(1, f1);
+  if (NTN <= 2 && n > 2) load(2, f2);
+  if (NTN <= 2) {
+    for (int blk = 0; blk < n; blk += 3) {
+      mac(f0);
+      if (blk + 3 < n) load(blk + 3, f0);
+      if (blk + 1 < n) { mac(f1); if (blk + 4 < n) load(blk + 4, f1); }
+      if (blk + 2 < n) { mac(f2); if (blk + 5 < n) load(blk + 5, f2); }
+    }
+  } else {
+    for (int blk = 0; blk < n; blk += 2) {
+      mac(f0);
+      if (blk + 2 < n) load(blk + 2, f0);
+      if (blk + 1 < n) { mac(f1); if (blk + 3 < n) load(blk + 3, f1); }
+    }
+  }
+
+  if (wave > 0) {
+#pragma unroll
+    for (int tn = 0; tn < NTN; ++tn)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) part[(((wave - 1) * NTN + tn) * 16 + i) * 64 + lane] = acc[tn][i];
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const int row = row0 + r;
+#pragma unroll
+    for (int tn = 0; tn < NTN; ++tn) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        float v = acc[tn][i];
+        for (int ws = 0; ws < KS - 1; ++ws) v += part[((ws * NTN + tn) * 16 + i) * 64 + lane];
+        acc[tn][i] = v;
+      }
+      if (row < T) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int col = tn * 32 + q * 8 + half * 4;
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr)
+            if (col + rr < E) logits[static_cast<int64_t>(row) * E + col + rr] = acc[tn][q * 4 + rr];
+        }
+      }
+    }
+  }
+}
+
+template <int NTN, int KS>
+int launch_router_direct(revive_ctx* ctx, const void* x, const void* w, float* logits, int T, hipStream_t stream) {
+  constexpr size_t lds = static_cast<size_t>(KS - 1) * NTN * 16 * 64 * sizeof(float);
+  auto kern = router_direct_kernel<NTN, KS>;
+  static bool configured = false;
+  if (!configured) {
+    REVIVE_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        static_cast<int>(lds)));
+    configured = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(ceil_div(T, 32)), dim3(64 * KS), lds, stream, static_cast<const uint16_t*>(x),
+                     static_cast<const uint16_t*>(w), logits, T, ctx->cfg.E, ctx->cfg.H);
+  return check_hip(ctx, hipGetLastError(), "router_direct launch");
+}
+
 }  // namespace
 
 int launch_router_gemm(revive_ctx* ctx, const void* x, const void* w, float* logits, int T, hipStream_t stream) {
   const revive_config& c = ctx->cfg;
   KernelTimer timer(ctx, REVIVE_K_ROUTER_GEMM, stream);
+  if (c.dtype == REVIVE_DTYPE_BF16 && c.E <= 128 && c.H % 256 == 0 &&
+      static_cast<int64_t>(ceil_div(T, 32)) * c.E * c.H * 2 <= (128ll << 20)) {
+    // small router: every 32-token workgroup re-reads the whole router matrix from L2
+    const bool ks8 = c.H % 512 == 0;
+    switch (ceil_div(c.E, 32)) {
+      case 1: return ks8 ? launch_router_direct<1, 8>(ctx, x, w, logits, T, stream) : launch_router_direct<1, 4>(ctx, x, w, logits, T, stream);
+      case 2: return ks8 ? launch_router_direct<2, 8>(ctx, x, w, logits, T, stream) : launch_router_direct<2, 4>(ctx, x, w, logits, T, stream);
+      case 3: return launch_router_direct<3, 4>(ctx, x, w, logits, T, stream);
+      default: return launch_router_direct<4, 4>(ctx, x, w, logits, T, stream);
+    }
+  }
   if (c.dtype == REVIVE_DTYPE_BF16) {
     GemmArgs a{};
     a.A = x; a.lda = c.H;
