@@ -24,12 +24,16 @@ constexpr int kTimingPairs = 8192;    // event pairs kept before timing results 
 constexpr int kTileM_bf16 = 256;
 constexpr int kTileM_f32 = 64;
 
-// One row-tile of a grouped GEMM: rows [row_begin, row_end) all belong to `group`.
+// One row-tile of a grouped GEMM.  All row-tiles of a group (physical slot) carry the same
+// record except for their position: tile j covers rows [group_begin + j*tile_m,
+// min(group_end, group_begin + (j+1)*tile_m)).  The group's weight matrices ride along so that a
+// workgroup needs one read to know everything about its tile.
 struct MTile {
   int32_t group;
-  int32_t row_begin;
-  int32_t row_end;
-  int32_t pad;  // (row-tiles of the group << 16) | position of this tile inside its group
+  int32_t group_begin;
+  int32_t group_end;
+  int32_t pad;          // (row-tiles of the group << 16) | position of this tile inside its group
+  const void* w[2];     // the group's gate/up and down matrices (null when the caller uses a table)
 };
 
 // Device-resident map, one contiguous blob at a fixed address so that one copy updates it.

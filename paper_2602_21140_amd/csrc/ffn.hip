@@ -16,6 +16,8 @@ namespace revive {
 namespace {
 
 __global__ __launch_bounds__(kMaxP) void ffn_tiles_kernel(const int32_t* __restrict__ slot_offsets, int P, int tile_m,
+                                                          const void* const* __restrict__ w_gate_up,
+                                                          const void* const* __restrict__ w_down,
                                                           MTile* __restrict__ tiles, int32_t* __restrict__ tile_count) {
   __shared__ int wave_sums[kMaxP / 64];
   const int p = threadIdx.x;
@@ -47,13 +49,17 @@ __global__ __launch_bounds__(kMaxP) void ffn_tiles_kernel(const int32_t* __restr
   }
   __syncthreads();
   const int base = wave_sums[wave] + incl - mine;
-  for (int i = 0; i < mine; ++i) {
+  if (mine > 0) {  // only slots that received rows have their weight pointers read
     MTile t;
     t.group = p;
-    t.row_begin = first + i * tile_m;
-    t.row_end = min(end, first + (i + 1) * tile_m);
-    t.pad = (mine << 16) | i;  // row-tiles of this slot, and this one's position among them
-    tiles[base + i] = t;
+    t.group_begin = first;
+    t.group_end = end;
+    t.w[0] = w_gate_up[p];
+    t.w[1] = w_down[p];
+    for (int i = 0; i < mine; ++i) {
+      t.pad = (mine << 16) | i;
+      tiles[base + i] = t;
+    }
   }
 }
 
@@ -80,6 +86,7 @@ GemmArgs gate_up_args(const revive_ctx* ctx, const Bf16Ffn& f, int bn_out) {
   a.n_out = f.I; a.K = ctx->cfg.H;
   a.tiles = f.tiles; a.tile_count = f.tile_count; a.M = f.M;
   a.n_col_tiles = ceil_div(f.I, bn_out);
+  a.b_sel = f.tiles ? 0 : -1;
   return a;
 }
 
@@ -91,6 +98,7 @@ GemmArgs down_args(const revive_ctx* ctx, const Bf16Ffn& f, int bn_out) {
   d.n_out = ctx->cfg.H; d.K = f.I;
   d.tiles = f.tiles; d.tile_count = f.tile_count; d.M = f.M;
   d.n_col_tiles = ceil_div(ctx->cfg.H, bn_out);
+  d.b_sel = f.tiles ? 1 : -1;
   return d;
 }
 
@@ -169,7 +177,8 @@ int launch_expert_ffn(revive_ctx* ctx, const void* x_perm, const int32_t* slot_o
   void* h = ctx->d_ws + ctx->ws.off_h;
   {
     KernelTimer timer(ctx, REVIVE_K_FFN_TILES, stream);
-    hipLaunchKernelGGL(ffn_tiles_kernel, dim3(1), dim3(kMaxP), 0, stream, slot_offsets, ctx->P, tile_m, tiles, tile_count);
+    hipLaunchKernelGGL(ffn_tiles_kernel, dim3(1), dim3(kMaxP), 0, stream, slot_offsets, ctx->P, tile_m, w_gate_up, w_down, tiles,
+                       tile_count);
     REVIVE_HIP(ctx, hipGetLastError());
   }
   const int bound = max_tiles(N, ctx->P, tile_m);

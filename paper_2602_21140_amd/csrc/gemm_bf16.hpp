@@ -56,6 +56,7 @@ struct GemmArgs {
   const int32_t* tile_count; // device count of valid entries in `tiles`
   int M;                     // dense case: number of rows
   int n_col_tiles;
+  int b_sel;                 // -1: weights from B_tab / B_one; 0 or 1: from the tile record's w[b_sel]
 };
 
 // Up to two independent problems served by one launch (e.g. the routed experts' grouped GEMM and
@@ -112,8 +113,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
   if (g.tiles) {
     const MTile t = g.tiles[m_idx];
     group = t.group;
-    row_begin = t.row_begin;
-    row_end = t.row_end;
+    row_begin = t.group_begin + (t.pad & 0xFFFF) * BM;
+    row_end = min(t.group_end, row_begin + BM);
   } else {
     row_begin = m_idx * BM;
     row_end = min(g.M, row_begin + BM);
@@ -347,26 +348,28 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   int m_idx = logical / g.n_col_tiles;
   int n_idx = logical - m_idx * g.n_col_tiles;
 
-  int group = 0, row_begin, row_end;
+  int row_begin, row_end;
+  const unsigned char* Bbase;
   if (g.tiles) {
-    // Inside one group's block of tiles the column index runs slowest: the row-tiles of a slot
-    // that use the same weight columns are neighbours in launch order and meet in L2.
-    MTile t = g.tiles[m_idx];
-    const int in_group = t.pad >> 16, first = m_idx - (t.pad & 0xFFFF);
+    // One read of any record of the group tells everything.  Inside one group's block of tiles
+    // the column index runs slowest: the row-tiles of a slot that use the same weight columns are
+    // neighbours in launch order and meet in L2.
+    const MTile t = g.tiles[m_idx];
+    const int in_group = t.pad >> 16;
+    int j = t.pad & 0xFFFF;
     if (in_group > 1) {
-      const int r = logical - first * g.n_col_tiles;
+      const int r = logical - (m_idx - j) * g.n_col_tiles;
       n_idx = r / in_group;
-      m_idx = first + (r - n_idx * in_group);
-      t = g.tiles[m_idx];
+      j = r - n_idx * in_group;
     }
-    group = t.group;
-    row_begin = t.row_begin;
-    row_end = t.row_end;
+    row_begin = t.group_begin + j * BM;
+    row_end = min(t.group_end, row_begin + BM);
+    Bbase = static_cast<const unsigned char*>(g.b_sel >= 0 ? t.w[g.b_sel] : (g.B_tab ? g.B_tab[t.group] : g.B_one));
   } else {
     row_begin = m_idx * BM;
     row_end = min(g.M, row_begin + BM);
+    Bbase = static_cast<const unsigned char*>(g.B_one);
   }
-  const unsigned char* Bbase = static_cast<const unsigned char*>(g.B_tab ? g.B_tab[group] : g.B_one);
   const unsigned char* Abase = static_cast<const unsigned char*>(g.A);
   const int n0 = n_idx * BN_OUT;
 
@@ -569,44 +572,51 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
     default: run(std::integral_constant<int, TM>{}); break;
   }
 
-  // ---- epilogue.  Lane holds, per 32x32 tile, for q = 0..3 the four columns
-  // q*8 + (lane/32)*4 + {0..3} of activation row lane % 32.
+  // ---- epilogue.  Per 32x32 tile a lane holds, for q = 0..3, the four columns
+  // q*8 + (lane/32)*4 + {0..3} of activation row lane % 32.  Each wavefront transposes its
+  // outputs through its own slice of LDS (padded rows: conflict-free 8-byte writes) and stores
+  // them to global memory as full 16-byte words, a whole row segment per group of lanes.
   constexpr int TN_OUT = EPI == EPI_SWIGLU ? TN / 2 : TN;
   constexpr int WN_OUT = EPI == EPI_SWIGLU ? WN / 2 : WN;
+  static_assert(EPI != EPI_F32, "this kernel stores bf16");
+  constexpr int ROWB = WN_OUT * 2 + 8;          // bytes between rows of the wavefront's LDS slice
+  constexpr int SLICE = TM * 32 * ROWB;
+  constexpr int LPR = WN_OUT * 2 / 16;          // lanes per row when reading back
+  constexpr int RPI = 64 / LPR;                 // rows per read-back instruction
+  __syncthreads();                              // every wavefront is done with the copy stages
+  unsigned char* slice = smem + wave * SLICE;
 #pragma unroll
   for (int tm = 0; tm < TM; ++tm) {
-    const int row = row_begin + (tm * WAVES_M + wm) * 32 + (lane & 31);
-    if (row >= row_end) continue;
+    if (tm >= tm_valid) break;
 #pragma unroll
     for (int tn = 0; tn < TN_OUT; ++tn) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int col = n0 + wn * WN_OUT + tn * 32 + q * 8 + (lane >> 5) * 4;
-        if (col >= g.n_out) continue;
         float v[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           if (EPI == EPI_SWIGLU) v[r] = silu_f32(acc[tm][tn][q * 4 + r]) * acc[tm][tn + TN / 2][q * 4 + r];
           else v[r] = acc[tm][tn][q * 4 + r];
         }
-        const int64_t off = static_cast<int64_t>(row) * g.ldc + col;
-        if (col + 3 < g.n_out && (g.ldc & 3) == 0) {
-          if (EPI == EPI_F32) {
-            f32x4 o = {v[0], v[1], v[2], v[3]};
-            *reinterpret_cast<f32x4*>(static_cast<float*>(g.C) + off) = o;
-          } else {
-            u32x2 o = {f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16),
-                       f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16)};
-            *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(g.C) + off) = o;
-          }
-        } else {
+        u32x2 o = {f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16),
+                   f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16)};
+        *reinterpret_cast<u32x2*>(slice + (tm * 32 + (lane & 31)) * ROWB + (tn * 32 + q * 8 + (lane >> 5) * 4) * 2) = o;
+      }
+    }
+  }
+  // read back: lane l takes 16 bytes (8 columns) of row l / LPR of each group of RPI rows
+  const int rcol = (lane % LPR) * 8;
+  const int col = n0 + wn * WN_OUT + rcol;
+  if (col < g.n_out) {  // n_out is a multiple of 8: a word is entirely inside or outside
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            if (col + r >= g.n_out) break;
-            if (EPI == EPI_F32) static_cast<float*>(g.C)[off + r] = v[r];
-            else static_cast<uint16_t*>(g.C)[off + r] = static_cast<uint16_t>(f32_to_bf16_bits(v[r]));
-          }
-        }
+    for (int it = 0; it < TM * 32 / RPI; ++it) {
+      const int lrow = it * RPI + lane / LPR;     // row inside the wavefront's slice
+      const int tm = lrow >> 5;
+      if (tm >= tm_valid) break;
+      const int row = row_begin + (tm * WAVES_M + wm) * 32 + (lrow & 31);
+      if (row < row_end) {
+        const u32x4 o = *reinterpret_cast<const u32x4*>(slice + lrow * ROWB + rcol * 2);
+        *reinterpret_cast<u32x4*>(static_cast<uint16_t*>(g.C) + static_cast<int64_t>(row) * g.ldc + col) = o;
       }
     }
   }
@@ -636,7 +646,10 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int KID, int STAGES
 int launch_gemm_bf16_dma(revive_ctx* ctx, const GemmArgs& p0, int max_m_tiles0, const GemmArgs* p1, int max_m_tiles1,
                          hipStream_t stream) {
   constexpr int NT = 64 * WAVES_M * WAVES_N;
-  constexpr size_t lds = STAGES * (BM + BN) * 64;
+  constexpr int WN_OUT_ = (EPI == EPI_SWIGLU ? BN / 2 : BN) / WAVES_N;
+  constexpr size_t lds_epi = static_cast<size_t>(WAVES_M * WAVES_N) * (BM / WAVES_M) * (WN_OUT_ * 2 + 8);
+  constexpr size_t lds_ring = STAGES * (BM + BN) * 64;
+  constexpr size_t lds = lds_ring > lds_epi ? lds_ring : lds_epi;
   auto kern = gemm_bf16_dma_kernel<BM, BN, WAVES_M, WAVES_N, EPI, KID, STAGES>;
   static bool configured = false;  // per instantiation
   if (!configured) {

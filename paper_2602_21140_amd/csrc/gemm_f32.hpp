@@ -42,8 +42,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32Args g) {
   if (g.tiles) {
     const MTile t = g.tiles[m_idx];
     group = t.group;
-    row_begin = t.row_begin;
-    row_end = t.row_end;
+    row_begin = t.group_begin + (t.pad & 0xFFFF) * BM;
+    row_end = min(t.group_end, row_begin + BM);
   } else {
     row_begin = m_idx * BM;
     row_end = min(g.M, row_begin + BM);
