@@ -318,6 +318,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   constexpr int CP = CP_A + CP_B;
   static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "copy split");
   static_assert(TM <= 4, "row sub-tile dispatch below covers up to four");
+  static_assert(STAGES >= 3 && STAGES <= 5, "prologue and tail are written for 2 to 4 steps of copy-ahead");
   static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU needs gate and up tiles in one wave");
   typedef __attribute__((address_space(1))) const void* gptr;
   typedef __attribute__((address_space(3))) void* lptr;
@@ -530,6 +531,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
     };
     // Tail: with j copies-ahead steps left, (j - 1) * CP copies may stay pending at the barrier.
     auto tail = [&](auto& fn, int& kt) {
+      if (D >= 4 && kt + 4 < KT) { fn(kt, F{}, std::integral_constant<int, 3 * CP>{}, F{}); ++kt; }
       if (D >= 3 && kt + 3 < KT) { fn(kt, F{}, std::integral_constant<int, 2 * CP>{}, F{}); ++kt; }
       if (D >= 2 && kt + 2 < KT) { fn(kt, F{}, std::integral_constant<int, CP>{}, F{}); ++kt; }
       if (kt + 1 < KT) { fn(kt, F{}, std::integral_constant<int, 0>{}, F{}); ++kt; }
@@ -541,6 +543,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
       int kt = 0;
       for (; kt + D < KT; ++kt) step(kt, T{}, std::integral_constant<int, VM_STEADY>{}, F{});
       // here kt + D >= KT: the copies of every remaining step are already issued
+      if (D >= 4 && kt + 3 < KT) { step(kt, F{}, std::integral_constant<int, 2 * CP>{}, F{}); ++kt; }
       if (D >= 3 && kt + 2 < KT) { step(kt, F{}, std::integral_constant<int, CP>{}, F{}); ++kt; }
       if (kt + 1 < KT) { step(kt, F{}, std::integral_constant<int, 0>{}, F{}); ++kt; }
       step(kt, F{}, std::integral_constant<int, 0>{}, T{});
@@ -557,8 +560,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   issue_copy(0);
   if (KT > 1) issue_copy(1);
   if (D >= 3 && KT > 2) issue_copy(2);
+  if (D >= 4 && KT > 3) issue_copy(3);
   asm volatile("" ::: "memory");
-  if (D >= 3 && KT > 2) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * CP));
+  if (D >= 4 && KT > 3) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(3 * CP));
+  else if (D >= 3 && KT > 2) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * CP));
   else if (KT > 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(CP));
   else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
   __builtin_amdgcn_s_barrier();
