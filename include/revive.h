@@ -126,6 +126,15 @@ int revive_set_placement(revive_ctx* ctx, const int32_t* phys_to_logical /*host*
 int revive_update_map(revive_ctx* ctx, const uint8_t* rank_failed /*host*/, revive_stream stream,
                       revive_map_stats* stats /*host, nullable*/);
 
+/* As revive_update_map, with experts that are failed individually as well
+ * (Sec. 4.2: a failed expert is treated as failed wherever it is chosen and is
+ * masked to -inf before the top-k).  expert_failed: host uint8[E], 1 = every
+ * replica of that expert is removed; NULL = none.  Rank and expert failures
+ * compose. */
+int revive_update_map_experts(revive_ctx* ctx, const uint8_t* rank_failed /*host*/,
+                              const uint8_t* expert_failed /*host, nullable*/, revive_stream stream,
+                              revive_map_stats* stats /*host, nullable*/);
+
 /* Copies of the current host-side tables (for tests): l2p_table int32
  * [E*max_replicas] (-1 padded), l2p_count int32[E], slot_alive uint8[P]. */
 int revive_get_map(const revive_ctx* ctx, int32_t* l2p_table /*host*/, int32_t* l2p_count /*host*/,
@@ -140,6 +149,26 @@ int revive_build_map(const revive_config* cfg /*host*/, const int32_t* phys_to_l
                      const uint8_t* rank_failed /*host,[R]*/, int32_t* l2p_table /*host*/,
                      int32_t* l2p_count /*host*/, uint8_t* slot_alive /*host*/,
                      revive_map_stats* stats /*host, nullable*/);
+
+int revive_build_map_experts(const revive_config* cfg /*host*/, const int32_t* phys_to_logical /*host,[P]*/,
+                             const uint8_t* rank_failed /*host,[R]*/, const uint8_t* expert_failed /*host,[E],nullable*/,
+                             int32_t* l2p_table /*host*/, int32_t* l2p_count /*host*/, uint8_t* slot_alive /*host*/,
+                             revive_map_stats* stats /*host, nullable*/);
+
+/* ---- lost-expert study (Sec. 4.2) ---------------------------------------- */
+
+/* "Every nth": mask[e] = 1 for the experts whose index is a multiple of n (n = 2
+ * fails every even-indexed expert), a fraction 1/n of them.  mask: host uint8[E]. */
+int revive_mask_every_nth(int32_t E, int32_t n, uint8_t* mask /*host*/);
+
+/* "Task-based": mask[e] = 1 for the n_fail most frequently activated experts
+ * (descending count, equal counts by ascending id).  counts: host int64[E]. */
+int revive_mask_most_activated(const int64_t* counts /*host*/, int32_t E, int32_t n_fail, uint8_t* mask /*host*/);
+
+/* Activation counting: counts[e] += number of times e appears in topk_logical
+ * [T, k].  counts: dev int64[E], accumulated (the caller zeroes it once; calls
+ * for several batches or layers add up).  Integer adds: order-independent. */
+int revive_expert_counts(revive_ctx* ctx, const int32_t* topk_logical, int32_t T, int64_t* counts, revive_stream stream);
 
 /* ---- data path ---------------------------------------------------------- */
 
@@ -238,6 +267,7 @@ enum {
   REVIVE_K_FFN_SHARED_GATE_UP,
   REVIVE_K_FFN_SHARED_DOWN,
   REVIVE_K_COMBINE,
+  REVIVE_K_EXPERT_COUNTS,
   REVIVE_K_COUNT
 };
 

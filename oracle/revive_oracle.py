@@ -52,12 +52,15 @@ class ExpertMap:
 
 
 def build_map(phys_to_logical: np.ndarray, rank_failed: np.ndarray, slots_per_rank: int,
-              E: int, max_replicas: int) -> ExpertMap:
+              E: int, max_replicas: int, expert_failed: Optional[np.ndarray] = None) -> ExpertMap:
     """Remove every replica that sits on a failed rank from the map.
 
     A slot p belongs to rank p // slots_per_rank.  Slot p survives when its
     rank is not failed and it holds an expert (phys_to_logical[p] >= 0).  For
     each logical expert the surviving slots are listed in ascending order.
+
+    `expert_failed` (Sec. 4.2: a failed expert i is treated as failed wherever
+    it is chosen) additionally removes every replica of the flagged experts.
     """
     p2l = np.asarray(phys_to_logical, dtype=np.int64)
     failed = np.asarray(rank_failed, dtype=np.uint8)
@@ -76,6 +79,8 @@ def build_map(phys_to_logical: np.ndarray, rank_failed: np.ndarray, slots_per_ra
         full[e] += 1
         if failed[p // slots_per_rank]:
             continue
+        if expert_failed is not None and expert_failed[e]:
+            continue
         alive[p] = 1
         assert count[e] < max_replicas, "more replicas than max_replicas"
         table[e, count[e]] = p
@@ -85,6 +90,44 @@ def build_map(phys_to_logical: np.ndarray, rank_failed: np.ndarray, slots_per_ra
                      n_live_experts=int((count > 0).sum()),
                      n_lost_experts=int((count == 0).sum()),
                      n_degraded_experts=int(((count > 0) & (count < full)).sum()))
+
+
+# --------------------------------------------------------------------------
+# Lost-expert study (Sec. 4.2): which experts to fail, and activation counts
+# --------------------------------------------------------------------------
+def every_nth_mask(E: int, n: int) -> np.ndarray:
+    """"Every nth": experts fail at a step of n, targeting a fraction 1/n.
+
+    The experts whose index is a multiple of n fail; n = 2 fails every
+    even-indexed expert, as the paper's example says.  uint8 [E].
+    """
+    assert n >= 1
+    m = np.zeros(E, dtype=np.uint8)
+    for e in range(E):
+        if e % n == 0:
+            m[e] = 1
+    return m
+
+
+def activation_counts(topk_logical: np.ndarray, E: int) -> np.ndarray:
+    """How often each expert was selected (int64 [E]); counts of several layers or batches add."""
+    c = np.zeros(E, dtype=np.int64)
+    for e in np.asarray(topk_logical).ravel():
+        c[int(e)] += 1
+    return c
+
+
+def most_activated_mask(counts: np.ndarray, n_fail: int) -> np.ndarray:
+    """"Task-based": fail the n_fail most frequently activated experts.
+
+    Experts are ranked by descending count, equal counts by ascending id.
+    """
+    counts = np.asarray(counts)
+    order = sorted(range(len(counts)), key=lambda e: (-int(counts[e]), e))
+    m = np.zeros(len(counts), dtype=np.uint8)
+    for e in order[:n_fail]:
+        m[e] = 1
+    return m
 
 
 def enough_live_experts(l2p_count: np.ndarray, k: int, n_group: int, topk_group: int) -> bool:

@@ -23,7 +23,7 @@ TORCH_DTYPE = {"fp32": torch.float32, "bf16": torch.bfloat16}
 
 KERNEL_NAMES = ["router_gemm", "route_topk", "dispatch_count", "dispatch_scan", "dispatch_place",
                 "dispatch_permute", "ffn_tiles", "ffn_gate_up", "ffn_down", "ffn_shared_gate_up",
-                "ffn_shared_down", "combine"]
+                "ffn_shared_down", "combine", "expert_counts"]
 
 
 class ReviveError(RuntimeError):
@@ -69,7 +69,12 @@ def lib() -> C.CDLL:
         "revive_bind_workspace": (C.c_int, [vp, vp, sz]),
         "revive_set_placement": (C.c_int, [vp, vp]),
         "revive_update_map": (C.c_int, [vp, vp, vp, P(MapStats)]),
+        "revive_update_map_experts": (C.c_int, [vp, vp, vp, vp, P(MapStats)]),
         "revive_get_map": (C.c_int, [vp, vp, vp, vp]),
+        "revive_build_map_experts": (C.c_int, [P(Config), vp, vp, vp, vp, vp, vp, P(MapStats)]),
+        "revive_mask_every_nth": (C.c_int, [i32, i32, vp]),
+        "revive_mask_most_activated": (C.c_int, [vp, i32, i32, vp]),
+        "revive_expert_counts": (C.c_int, [vp, vp, i32, vp, vp]),
         "revive_build_map": (C.c_int, [P(Config), vp, vp, vp, vp, vp, P(MapStats)]),
         "revive_route": (C.c_int, [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]),
         "revive_dispatch": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp, vp]),
@@ -97,7 +102,8 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ["revive_create", "revive_destroy", "revive_workspace_bytes", "revive_bind_workspace",
-           "revive_set_placement", "revive_update_map", "revive_get_map", "revive_build_map",
+           "revive_set_placement", "revive_update_map", "revive_update_map_experts", "revive_get_map", "revive_build_map",
+           "revive_build_map_experts", "revive_mask_every_nth", "revive_mask_most_activated", "revive_expert_counts",
            "revive_route", "revive_dispatch", "revive_expert_ffn", "revive_shared_ffn", "revive_combine",
            "revive_graph_begin", "revive_graph_end", "revive_graph_launch", "revive_graph_exec_id",
            "revive_graph_destroy", "revive_set_kernel_timing", "revive_kernel_time",
@@ -116,8 +122,28 @@ def make_config(cfg, T_max: Optional[int] = None, route_scale: float = 1.0) -> C
                   topk_group=cfg.topk_group, dtype=DTYPE[cfg.dtype], route_scale=route_scale)
 
 
-def build_map_host(cfg, phys_to_logical: np.ndarray, rank_failed: np.ndarray, route_scale: float = 1.0):
-    """revive_build_map: the library's host-side map construction, no GPU needed.
+def mask_every_nth(E: int, n: int) -> np.ndarray:
+    """revive_mask_every_nth: uint8[E], 1 for the experts whose index is a multiple of n."""
+    m = np.zeros(E, dtype=np.uint8)
+    rc = lib().revive_mask_every_nth(E, n, m.ctypes.data)
+    if rc != 0:
+        raise ReviveError(rc, lib().revive_last_error(None).decode())
+    return m
+
+
+def mask_most_activated(counts: np.ndarray, n_fail: int) -> np.ndarray:
+    """revive_mask_most_activated: uint8[E], 1 for the n_fail most frequently activated experts."""
+    c = np.ascontiguousarray(counts, dtype=np.int64)
+    m = np.zeros(c.shape[0], dtype=np.uint8)
+    rc = lib().revive_mask_most_activated(c.ctypes.data, c.shape[0], n_fail, m.ctypes.data)
+    if rc != 0:
+        raise ReviveError(rc, lib().revive_last_error(None).decode())
+    return m
+
+
+def build_map_host(cfg, phys_to_logical: np.ndarray, rank_failed: np.ndarray, route_scale: float = 1.0,
+                   expert_failed: Optional[np.ndarray] = None):
+    """revive_build_map(_experts): the library's host-side map construction, no GPU needed.
 
     Returns (status, l2p_table [E, max_replicas], l2p_count [E], slot_alive [P], stats dict)."""
     c = make_config(cfg, route_scale=route_scale)
@@ -128,8 +154,10 @@ def build_map_host(cfg, phys_to_logical: np.ndarray, rank_failed: np.ndarray, ro
     count = np.zeros(cfg.E, dtype=np.int32)
     alive = np.zeros(p2l.shape[0], dtype=np.uint8)
     stats = MapStats()
-    rc = lib().revive_build_map(C.byref(c), p2l.ctypes.data, failed.ctypes.data, table.ctypes.data,
-                                count.ctypes.data, alive.ctypes.data, C.byref(stats))
+    ef = None if expert_failed is None else np.ascontiguousarray(expert_failed, dtype=np.uint8)
+    rc = lib().revive_build_map_experts(C.byref(c), p2l.ctypes.data, failed.ctypes.data,
+                                        None if ef is None else ef.ctypes.data, table.ctypes.data,
+                                        count.ctypes.data, alive.ctypes.data, C.byref(stats))
     return rc, table, count, alive, stats.as_dict()
 
 
@@ -206,12 +234,25 @@ class ReviveLayer:
         self.phys_to_logical = p2l
         self._check(self.L.revive_set_placement(self._ctx, p2l.ctypes.data))
 
-    def update_map(self, rank_failed: np.ndarray, stream=None) -> Dict[str, int]:
+    def update_map(self, rank_failed: np.ndarray, stream=None, expert_failed: Optional[np.ndarray] = None) -> Dict[str, int]:
         failed = np.ascontiguousarray(rank_failed, dtype=np.uint8)
         assert failed.shape == (self.cfg.n_ranks,)
         stats = MapStats()
-        self._check(self.L.revive_update_map(self._ctx, failed.ctypes.data, self._stream(stream), C.byref(stats)))
+        if expert_failed is None:
+            self._check(self.L.revive_update_map(self._ctx, failed.ctypes.data, self._stream(stream), C.byref(stats)))
+        else:
+            ef = np.ascontiguousarray(expert_failed, dtype=np.uint8)
+            assert ef.shape == (self.cfg.E,)
+            self._check(self.L.revive_update_map_experts(self._ctx, failed.ctypes.data, ef.ctypes.data,
+                                                         self._stream(stream), C.byref(stats)))
         return stats.as_dict()
+
+    def expert_counts(self, topk_logical, T: int, counts=None, stream=None):
+        """counts[e] += activations of e in topk_logical [T, k]; counts: int64 [E] on the device."""
+        if counts is None:
+            counts = torch.zeros(self.cfg.E, dtype=torch.int64, device=self.device)
+        self._check(self.L.revive_expert_counts(self._ctx, _ptr(topk_logical), T, _ptr(counts), self._stream(stream)))
+        return counts
 
     def update_map_status(self, rank_failed: np.ndarray, stream=None) -> int:
         """As update_map but returns the status code instead of raising."""

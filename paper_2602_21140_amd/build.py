@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "librevive.so")
-SOURCES = ["api.hip", "route.hip", "dispatch.hip", "ffn.hip", "combine.hip"]
+SOURCES = ["api.hip", "route.hip", "dispatch.hip", "ffn.hip", "combine.hip", "study.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",

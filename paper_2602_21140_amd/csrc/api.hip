@@ -79,10 +79,13 @@ static bool enough_live(const revive_config& c, const int32_t* count) {
 // Writes count[E], table[E * max_replicas] (-1 padded) and alive[P]; all three must be zeroed by
 // the caller except table, which is filled here.  `who` receives the error text (may be null).
 static int build_tables(const revive_ctx* who, const revive_config& c, const int32_t* p2l, const uint8_t* rank_failed,
-                        int32_t* count, int32_t* table, uint8_t* alive, revive_map_stats* stats) {
+                        const uint8_t* expert_failed, int32_t* count, int32_t* table, uint8_t* alive, revive_map_stats* stats) {
   const int P = c.n_ranks * c.slots_per_rank;
   for (int r = 0; r < c.n_ranks; ++r)
     if (rank_failed[r] > 1) return fail(who, REVIVE_EINVAL, "rank_failed[%d] = %d is not 0 or 1", r, rank_failed[r]);
+  if (expert_failed)
+    for (int e = 0; e < c.E; ++e)
+      if (expert_failed[e] > 1) return fail(who, REVIVE_EINVAL, "expert_failed[%d] = %d is not 0 or 1", e, expert_failed[e]);
   std::vector<int32_t> full(c.E, 0);
   std::fill(count, count + c.E, 0);
   std::fill(alive, alive + P, 0);
@@ -94,6 +97,7 @@ static int build_tables(const revive_ctx* who, const revive_config& c, const int
     if (e < 0) continue;
     if (++full[e] > c.max_replicas) return fail(who, REVIVE_EINVAL, "expert %d has more than max_replicas = %d copies", e, c.max_replicas);
     if (rank_failed[p / c.slots_per_rank]) continue;
+    if (expert_failed && expert_failed[e]) continue;
     alive[p] = 1;
     table[static_cast<size_t>(e) * c.max_replicas + count[e]++] = p;
     ++st.n_live_slots;
@@ -249,6 +253,11 @@ int revive_set_placement(revive_ctx* ctx, const int32_t* phys_to_logical) {
 }
 
 int revive_update_map(revive_ctx* ctx, const uint8_t* rank_failed, revive_stream stream, revive_map_stats* stats) {
+  return revive_update_map_experts(ctx, rank_failed, nullptr, stream, stats);
+}
+
+int revive_update_map_experts(revive_ctx* ctx, const uint8_t* rank_failed, const uint8_t* expert_failed, revive_stream stream,
+                              revive_map_stats* stats) {
   if (!ctx || !rank_failed) return fail(ctx, REVIVE_EINVAL, "revive_update_map: null argument");
   if (!ctx->placement_set) return fail(ctx, REVIVE_ESTATE, "revive_update_map: call revive_set_placement first");
   const revive_config& c = ctx->cfg;
@@ -256,7 +265,7 @@ int revive_update_map(revive_ctx* ctx, const uint8_t* rank_failed, revive_stream
   // Build the new tables aside; nothing is committed until validation has passed.
   std::vector<uint8_t> blob(ctx->map.bytes, 0);
   revive_map_stats st{0, 0, 0, 0};
-  int rc = build_tables(ctx, c, ctx->phys_to_logical.data(), rank_failed,
+  int rc = build_tables(ctx, c, ctx->phys_to_logical.data(), rank_failed, expert_failed,
                         reinterpret_cast<int32_t*>(blob.data() + ctx->map.off_count),
                         reinterpret_cast<int32_t*>(blob.data() + ctx->map.off_table), blob.data() + ctx->map.off_alive, &st);
   if (rc != REVIVE_OK) return rc;
@@ -287,11 +296,33 @@ int revive_get_map(const revive_ctx* ctx, int32_t* l2p_table, int32_t* l2p_count
 
 int revive_build_map(const revive_config* cfg, const int32_t* phys_to_logical, const uint8_t* rank_failed,
                      int32_t* l2p_table, int32_t* l2p_count, uint8_t* slot_alive, revive_map_stats* stats) {
+  return revive_build_map_experts(cfg, phys_to_logical, rank_failed, nullptr, l2p_table, l2p_count, slot_alive, stats);
+}
+
+int revive_mask_every_nth(int32_t E, int32_t n, uint8_t* mask) {
+  if (E <= 0 || n <= 0 || !mask) return fail(nullptr, REVIVE_EINVAL, "revive_mask_every_nth: bad argument");
+  for (int e = 0; e < E; ++e) mask[e] = e % n == 0;
+  return REVIVE_OK;
+}
+
+int revive_mask_most_activated(const int64_t* counts, int32_t E, int32_t n_fail, uint8_t* mask) {
+  if (!counts || !mask || E <= 0 || n_fail < 0 || n_fail > E) return fail(nullptr, REVIVE_EINVAL, "revive_mask_most_activated: bad argument");
+  std::vector<int> order(E);
+  for (int e = 0; e < E; ++e) order[e] = e;
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return counts[a] > counts[b]; });  // stable: ties by id
+  std::fill(mask, mask + E, 0);
+  for (int i = 0; i < n_fail; ++i) mask[order[i]] = 1;
+  return REVIVE_OK;
+}
+
+int revive_build_map_experts(const revive_config* cfg, const int32_t* phys_to_logical, const uint8_t* rank_failed,
+                             const uint8_t* expert_failed, int32_t* l2p_table, int32_t* l2p_count, uint8_t* slot_alive,
+                             revive_map_stats* stats) {
   if (!cfg || !phys_to_logical || !rank_failed || !l2p_table || !l2p_count || !slot_alive)
     return fail(nullptr, REVIVE_EINVAL, "revive_build_map: null argument");
   int rc = check_config(*cfg);
   if (rc != REVIVE_OK) return rc;
-  return build_tables(nullptr, *cfg, phys_to_logical, rank_failed, l2p_count, l2p_table, slot_alive, stats);
+  return build_tables(nullptr, *cfg, phys_to_logical, rank_failed, expert_failed, l2p_count, l2p_table, slot_alive, stats);
 }
 
 // ---- data path entry points: argument checks, then the stage's launcher ----
@@ -351,6 +382,15 @@ int revive_shared_ffn(revive_ctx* ctx, const void* x, const void* w_sh_gate_up, 
   if (T == 0) return REVIVE_OK;
   if (!x || !w_sh_gate_up || !w_sh_down || !y_shared) return fail(ctx, REVIVE_EINVAL, "revive_shared_ffn: null argument");
   return launch_shared_ffn(ctx, x, w_sh_gate_up, w_sh_down, y_shared, T, static_cast<hipStream_t>(stream));
+}
+
+int revive_expert_counts(revive_ctx* ctx, const int32_t* topk_logical, int32_t T, int64_t* counts, revive_stream stream) {
+  int rc = check_call(ctx, "revive_expert_counts", T, false);
+  if (rc != REVIVE_OK) return rc;
+  if (!counts) return fail(ctx, REVIVE_EINVAL, "revive_expert_counts: null counts");
+  if (T == 0) return REVIVE_OK;
+  if (!topk_logical) return fail(ctx, REVIVE_EINVAL, "revive_expert_counts: null argument");
+  return launch_expert_counts(ctx, topk_logical, T, counts, static_cast<hipStream_t>(stream));
 }
 
 int revive_combine(revive_ctx* ctx, const void* y_perm, const int32_t* dst_row, const float* topk_weight,
@@ -459,7 +499,7 @@ int revive_reset_kernel_times(revive_ctx* ctx) {
 const char* revive_kernel_name(int32_t kernel) {
   static const char* names[REVIVE_K_COUNT] = {
       "router_gemm", "route_topk", "dispatch_count", "dispatch_scan", "dispatch_place", "dispatch_permute",
-      "ffn_tiles", "ffn_gate_up", "ffn_down", "ffn_shared_gate_up", "ffn_shared_down", "combine"};
+      "ffn_tiles", "ffn_gate_up", "ffn_down", "ffn_shared_gate_up", "ffn_shared_down", "combine", "expert_counts"};
   return kernel >= 0 && kernel < REVIVE_K_COUNT ? names[kernel] : "?";
 }
 

@@ -135,6 +135,7 @@ int launch_expert_ffn(revive_ctx*, const void* x_perm, const int32_t* slot_offse
                       const void* w_sh_down, void* y_shared, int T, hipStream_t);
 int launch_shared_ffn(revive_ctx*, const void* x, const void* w_sh_gate_up, const void* w_sh_down, void* y_shared, int T,
                       hipStream_t);
+int launch_expert_counts(revive_ctx*, const int32_t* topk_logical, int T, int64_t* counts, hipStream_t);
 int launch_combine(revive_ctx*, const void* y_perm, const int32_t* dst_row, const float* topk_weight,
                    const void* y_shared, int T, void* out, hipStream_t);
 

@@ -26,6 +26,7 @@ class ResidentLayer:
         self.p2l = synth.make_placement(cfg)
         self.layer.set_placement(self.p2l)
         self.failed = synth.failed_mask(cfg, failed)
+        self.expert_failed = None
         self.stats = self.layer.update_map(self.failed)
         self.x = synth.draw_x(cfg, device)
         self.w_router = synth.draw_router(cfg, device)        # [H, E]
@@ -62,9 +63,10 @@ class ResidentLayer:
         self._ev_fork = torch.cuda.Event()
         self._ev_join = torch.cuda.Event()
 
-    def set_failed(self, failed: Iterable[int], stream=None) -> Dict[str, int]:
+    def set_failed(self, failed: Iterable[int], stream=None, expert_failed=None) -> Dict[str, int]:
         self.failed = synth.failed_mask(self.cfg, failed)
-        self.stats = self.layer.update_map(self.failed, stream=stream)
+        self.expert_failed = expert_failed
+        self.stats = self.layer.update_map(self.failed, stream=stream, expert_failed=expert_failed)
         return self.stats
 
     def forward(self, logits: Optional[torch.Tensor] = None, shared=True, stream=None,

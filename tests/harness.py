@@ -31,7 +31,8 @@ class GpuLayer(ResidentLayer):
     # ---- oracle-side views of the same bits ------------------------------------------------
     def oracle_map(self) -> orc.ExpertMap:
         c = self.cfg
-        return orc.build_map(self.p2l, self.failed, c.slots_per_rank, c.E, c.max_replicas)
+        return orc.build_map(self.p2l, self.failed, c.slots_per_rank, c.E, c.max_replicas,
+                             expert_failed=self.expert_failed)
 
     def expert_f64(self, e: int) -> Dict[str, np.ndarray]:
         """Expert e's matrices in math layout, fp64, read back from the first slot that holds it."""

@@ -91,3 +91,37 @@ def test_host_map_build_rejects_bad_input():
     assert pk.build_map_host(g, pg, failed)[0] == -4     # 1 + 2 < 4
     failed[[1, 2]] = 0
     assert pk.build_map_host(g, pg, failed)[0] == 0      # groups hold 3, 2, 4, 4: worst pair 2 + 3 >= 4
+
+
+def test_mask_generators_match_oracle():
+    pk = _pk()
+    for E, n in ((8, 2), (256, 32), (384, 64), (10, 3), (6, 1)):
+        assert np.array_equal(pk.mask_every_nth(E, n), orc.every_nth_mask(E, n))
+    rng = np.random.default_rng(9)
+    for _ in range(30):
+        E = int(rng.integers(1, 60))
+        counts = rng.integers(0, 5, size=E)          # many ties
+        n_fail = int(rng.integers(0, E + 1))
+        assert np.array_equal(pk.mask_most_activated(counts, n_fail), orc.most_activated_mask(counts, n_fail))
+
+
+def test_host_map_build_with_failed_experts_matches_oracle():
+    pk = _pk()
+    rng = np.random.default_rng(11)
+    for name in ("c1", "c3", "c5"):
+        cfg = synth.get_config(name)
+        p2l = synth.make_placement(cfg)
+        for n in (2, 4, 64):
+            if name == "c1" and n > 4:
+                continue
+            ef = orc.every_nth_mask(cfg.E, n)
+            for failed in (synth.failed_mask(cfg, []), synth.failed_mask(cfg)):
+                rc, table, count, alive, stats = pk.build_map_host(cfg, p2l, failed, expert_failed=ef)
+                m = orc.build_map(p2l, failed, cfg.slots_per_rank, cfg.E, cfg.max_replicas, expert_failed=ef)
+                assert (rc == 0) == orc.enough_live_experts(m.l2p_count, cfg.k, cfg.n_group, cfg.topk_group)
+                assert np.array_equal(table, m.l2p_table) and np.array_equal(count, m.l2p_count)
+                assert np.array_equal(alive, m.slot_alive) and stats["n_lost_experts"] == m.n_lost_experts
+    bad = np.zeros(16, np.uint8)
+    bad[3] = 7
+    cfg = synth.get_config("c1")
+    assert pk.build_map_host(cfg, synth.make_placement(cfg), synth.failed_mask(cfg, []), expert_failed=bad)[0] == -1

@@ -1,0 +1,118 @@
+"""GPU tests of what follows the hot path in the paper: a failed rank's slots coming back
+(Sec. 3.4 "Role switch", Sec. 4.3) and the lost-expert study's masks and activation counts (Sec. 4.2)."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import revive_oracle as orc
+from harness import GpuLayer, TOL, f64, rel_err
+
+pytestmark = pytest.mark.gpu
+
+CFG = synth.scaled(synth.get_config("c4"), T=900, H=512, I=256, I_shared=256)
+
+
+def _i(t):
+    return t.cpu().numpy()
+
+
+def _experts_f64(g):
+    return {e: g.expert_f64(e) for e in range(g.cfg.E)}
+
+
+def test_failed_rank_is_never_read_and_comes_back():
+    """While a rank is failed its weights may be garbage (the device is lost) and must not be
+    touched; after new weights have been written in the background and the rank is un-failed,
+    the masked experts return and the output is the unfailed layer's."""
+    cfg = CFG
+    g = GpuLayer(cfg, failed=[])
+    try:
+        experts = _experts_f64(g)
+        base = orc.layer_staged(f64(g.x), f64(g.w_router), experts, g.shared_f64(), g.p2l, g.oracle_map(), cfg.k,
+                                cfg.score_fn, cfg.n_group, cfg.topk_group)
+        S = cfg.slots_per_rank
+        lost_slots = [p for r in cfg.failed_ranks for p in range(r * S, (r + 1) * S)]
+        saved = {p: (g.gu[p].clone(), g.dn[p].clone()) for p in lost_slots}
+        stats = g.set_failed(cfg.failed_ranks)
+        assert stats["n_lost_experts"] == 5
+        for p in lost_slots:                     # the failed devices' memory is gone
+            g.gu[p].fill_(float("nan"))
+            g.dn[p].fill_(float("nan"))
+        r = g.forward()
+        out_failed = r["out"].clone()
+        assert torch.isfinite(out_failed.float()).all()
+        tr = orc.layer_staged(f64(g.x), None, experts, g.shared_f64(), g.p2l, g.oracle_map(), cfg.k, cfg.score_fn,
+                              cfg.n_group, cfg.topk_group, logits=f64(r["logits"]))
+        assert np.array_equal(_i(r["topk_phys"]), tr.topk_phys)
+        assert rel_err(f64(out_failed), tr.out) < TOL[cfg.dtype]
+        # role switch: replacement weights arrive on a side stream while the layer keeps serving
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            for p in lost_slots:
+                g.gu[p].copy_(saved[p][0], non_blocking=True)
+                g.dn[p].copy_(saved[p][1], non_blocking=True)
+        r = g.forward()                          # still under the failure map: unaffected by the copies
+        assert torch.equal(r["out"], out_failed)
+        side.synchronize()
+        stats = g.set_failed([])
+        assert stats["n_lost_experts"] == 0 and stats["n_live_slots"] == cfg.P
+        r = g.forward()
+        assert np.array_equal(_i(r["topk_logical"]), orc.select_topk(
+            orc.masked_selection_scores(orc.scores(f64(r["logits"]), cfg.score_fn), g.oracle_map().l2p_count),
+            cfg.k, cfg.n_group, cfg.topk_group))
+        assert rel_err(f64(r["out"]), base.out) < TOL[cfg.dtype]
+    finally:
+        g.close()
+
+
+@pytest.mark.parametrize("n", [2, 4, 32])
+def test_every_nth_masks_on_the_gpu(n):
+    import paper_2602_21140_amd as pk
+    cfg = CFG
+    g = GpuLayer(cfg, failed=[], with_weights=False)
+    try:
+        mask = pk.mask_every_nth(cfg.E, n)
+        assert np.array_equal(mask, orc.every_nth_mask(cfg.E, n))
+        stats = g.set_failed([], expert_failed=mask)
+        assert stats["n_lost_experts"] == cfg.E // n
+        logits = synth.draw_logits(cfg, g.device)
+        _, top_l, top_w, top_p = g.layer.route(None, None, cfg.T, logits=logits, logits_given=True)
+        m = g.oracle_map()
+        s = orc.scores(f64(logits), cfg.score_fn)
+        ref = orc.select_topk(orc.masked_selection_scores(s, m.l2p_count), cfg.k, cfg.n_group, cfg.topk_group)
+        assert np.array_equal(_i(top_l), ref)
+        assert np.array_equal(_i(top_p), orc.remap(ref, m))
+        assert not mask[_i(top_l)].any()
+        if n == 2:
+            assert np.all(_i(top_l) % 2 == 1)    # Sec. 4.2: every even-indexed expert has failed
+    finally:
+        g.close()
+
+
+def test_task_based_mask_from_gpu_activation_counts():
+    import paper_2602_21140_amd as pk
+    cfg = CFG
+    g = GpuLayer(cfg, failed=[], with_weights=False)
+    try:
+        L = g.layer
+        counts = torch.zeros(cfg.E, dtype=torch.int64, device=g.device)
+        ref_counts = np.zeros(cfg.E, dtype=np.int64)
+        for layer in range(3):                   # "aggregate the counts across layers"
+            logits = synth.draw_logits(synth.scaled(cfg, seed=layer + 1), g.device)
+            _, top_l, _, _ = L.route(None, None, cfg.T, logits=logits, logits_given=True)
+            L.expert_counts(top_l, cfg.T, counts=counts)
+            ref_counts += orc.activation_counts(_i(top_l), cfg.E)
+        assert np.array_equal(_i(counts), ref_counts) and ref_counts.sum() == 3 * cfg.T * cfg.k
+        for frac in (64, 32, 8):
+            n_fail = cfg.E // frac
+            mask = pk.mask_most_activated(_i(counts), n_fail)
+            assert np.array_equal(mask, orc.most_activated_mask(ref_counts, n_fail))
+            stats = g.set_failed([], expert_failed=mask)
+            assert stats["n_lost_experts"] == n_fail
+            logits = synth.draw_logits(cfg, g.device)
+            _, top_l, top_w, _ = L.route(None, None, cfg.T, logits=logits, logits_given=True)
+            assert not mask[_i(top_l)].any()
+            assert np.abs(f64(top_w).sum(axis=1) - 1).max() < 1e-6
+    finally:
+        g.close()

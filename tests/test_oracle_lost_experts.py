@@ -1,0 +1,74 @@
+"""Pins for the oracle's lost-expert study helpers (Sec. 4.2 of the paper)."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import revive_oracle as orc
+
+
+def test_every_nth_examples():
+    # the paper's example: r = 1/2 fails every even-indexed expert
+    assert orc.every_nth_mask(8, 2).tolist() == [1, 0, 1, 0, 1, 0, 1, 0]
+    assert orc.every_nth_mask(8, 4).tolist() == [1, 0, 0, 0, 1, 0, 0, 0]
+    assert orc.every_nth_mask(6, 1).tolist() == [1] * 6
+    for n in (2, 4, 8, 16, 32, 64):
+        m = orc.every_nth_mask(256, n)
+        assert m.sum() * n == 256                      # exactly the target fraction 1/n
+        assert np.all(np.diff(np.nonzero(m)[0]) == n)  # a constant step
+
+
+def test_every_nth_half_routes_only_to_odd_experts():
+    cfg = synth.get_config("c1")
+    p2l = synth.make_placement(cfg)
+    mask = orc.every_nth_mask(cfg.E, 2)
+    m = orc.build_map(p2l, synth.failed_mask(cfg, []), cfg.slots_per_rank, cfg.E, cfg.max_replicas, expert_failed=mask)
+    assert m.n_lost_experts == cfg.E // 2
+    assert np.array_equal(m.l2p_count > 0, mask == 0)
+    assert not m.slot_alive[np.isin(p2l, np.nonzero(mask)[0])].any()
+    s = orc.scores(synth.draw_logits(cfg).numpy(), "softmax")
+    top = orc.select_topk(orc.masked_selection_scores(s, m.l2p_count), cfg.k)
+    assert np.all(top % 2 == 1)
+
+
+def test_expert_and_rank_failures_compose():
+    cfg = synth.get_config("c1")
+    p2l = synth.make_placement(cfg)
+    mask = np.zeros(cfg.E, np.uint8)
+    mask[[0, 8]] = 1
+    both = orc.build_map(p2l, synth.failed_mask(cfg), cfg.slots_per_rank, cfg.E, cfg.max_replicas, expert_failed=mask)
+    ranks_only = orc.build_map(p2l, synth.failed_mask(cfg), cfg.slots_per_rank, cfg.E, cfg.max_replicas)
+    assert both.l2p_count[0] == 0 and both.l2p_count[8] == 0
+    keep = np.ones(cfg.E, bool)
+    keep[[0, 8]] = False
+    assert np.array_equal(both.l2p_count[keep], ranks_only.l2p_count[keep])
+    assert np.array_equal(both.l2p_table[keep], ranks_only.l2p_table[keep])
+    assert both.n_lost_experts == ranks_only.n_lost_experts + 2
+
+
+def test_activation_counts_match_bincount():
+    r = np.random.default_rng(0)
+    top = r.integers(0, 37, size=(500, 6))
+    c = orc.activation_counts(top, 37)
+    assert c.sum() == top.size
+    assert np.array_equal(c, np.bincount(top.ravel(), minlength=37))
+    assert orc.activation_counts(np.zeros((0, 4), np.int32), 5).tolist() == [0] * 5
+
+
+def test_most_activated_mask_properties():
+    counts = np.array([5, 9, 9, 1, 0, 9, 3, 5])
+    assert orc.most_activated_mask(counts, 0).sum() == 0
+    assert orc.most_activated_mask(counts, 2).tolist() == [0, 1, 1, 0, 0, 0, 0, 0]      # tie of three 9s: lower ids
+    assert orc.most_activated_mask(counts, 4).tolist() == [1, 1, 1, 0, 0, 1, 0, 0]      # then the first 5
+    r = np.random.default_rng(1)
+    for _ in range(20):
+        c = r.integers(0, 6, size=24)
+        n = int(r.integers(0, 25))
+        m = orc.most_activated_mask(c, n)
+        assert m.sum() == n
+        if 0 < n < 24:
+            assert c[m == 1].min() >= c[m == 0].max()   # no survivor is more activated than a failed expert
+            # brute force: the lexicographically first set among those with the largest total count
+            worst_in = c[m == 1].min()
+            tied_in = [e for e in range(24) if m[e] and c[e] == worst_in]
+            tied_out = [e for e in range(24) if not m[e] and c[e] == worst_in]
+            assert not tied_out or max(tied_in) < min(tied_out)
