@@ -170,6 +170,18 @@ int revive_mask_most_activated(const int64_t* counts /*host*/, int32_t E, int32_
  * for several batches or layers add up).  Integer adds: order-independent. */
 int revive_expert_counts(revive_ctx* ctx, const int32_t* topk_logical, int32_t T, int64_t* counts, revive_stream stream);
 
+/* ---- logical-rank compaction (Sec. 3.5) ----------------------------------- */
+
+/* New logical ranks of a communication domain after device `failed_device`
+ * fails.  logical_rank: host int32[n], in/out, -1 = device not in the domain.
+ * Without a role switch (switched_device < 0) the device holding the next rank
+ * takes the failed one's rank and every later rank is decremented.  With a role
+ * switch, switched_device takes the failed device's rank and the gap it leaves
+ * behind (if it had a rank) is closed the same way.  Pure host function; on this
+ * one-GPU build the rank-segmented buffers need no compaction (a failed rank's
+ * segment is simply empty), so nothing on the data path consumes the result. */
+int revive_compact_ranks(int32_t* logical_rank /*host*/, int32_t n, int32_t failed_device, int32_t switched_device);
+
 /* ---- data path ---------------------------------------------------------- */
 
 /* a1..a5 - Gate (Sec. 2.1), failure mask (Sec. 3.4 "Missing experts", Sec. 4.2)

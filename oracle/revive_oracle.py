@@ -130,6 +130,35 @@ def most_activated_mask(counts: np.ndarray, n_fail: int) -> np.ndarray:
     return m
 
 
+# --------------------------------------------------------------------------
+# Logical-rank compaction (Sec. 3.5 "Recreating Communications")
+# --------------------------------------------------------------------------
+def compact_ranks(logical_rank: Sequence[int], failed_device: int, switched_device: int = -1) -> List[int]:
+    """New logical ranks after one device fails.
+
+    `logical_rank[d]` is device d's current logical rank (-1 = not in the
+    domain).  Without a role switch the failed device leaves a gap: the device
+    that had the next rank takes its rank and every later rank is decremented.
+    With a role switch, device `switched_device` (in the domain or not) takes
+    the failed device's rank; the gap it leaves behind, if it had a rank, is
+    closed the same way.  The failed device ends with rank -1.
+    """
+    ranks = list(logical_rank)
+    gap = ranks[failed_device]
+    assert gap >= 0, "the failed device had no rank"
+    ranks[failed_device] = -1
+    if switched_device >= 0:
+        assert switched_device != failed_device
+        old = ranks[switched_device]
+        ranks[switched_device] = gap
+        gap = old                       # the rank the switched device gives up (-1: none)
+    if gap >= 0:
+        for d in range(len(ranks)):
+            if ranks[d] > gap:
+                ranks[d] -= 1
+    return ranks
+
+
 def enough_live_experts(l2p_count: np.ndarray, k: int, n_group: int, topk_group: int) -> bool:
     """True when every token can always be given k live experts.
 

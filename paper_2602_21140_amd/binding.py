@@ -72,6 +72,7 @@ def lib() -> C.CDLL:
         "revive_update_map_experts": (C.c_int, [vp, vp, vp, vp, P(MapStats)]),
         "revive_get_map": (C.c_int, [vp, vp, vp, vp]),
         "revive_build_map_experts": (C.c_int, [P(Config), vp, vp, vp, vp, vp, vp, P(MapStats)]),
+        "revive_compact_ranks": (C.c_int, [vp, i32, i32, i32]),
         "revive_mask_every_nth": (C.c_int, [i32, i32, vp]),
         "revive_mask_most_activated": (C.c_int, [vp, i32, i32, vp]),
         "revive_expert_counts": (C.c_int, [vp, vp, i32, vp, vp]),
@@ -103,7 +104,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ["revive_create", "revive_destroy", "revive_workspace_bytes", "revive_bind_workspace",
            "revive_set_placement", "revive_update_map", "revive_update_map_experts", "revive_get_map", "revive_build_map",
-           "revive_build_map_experts", "revive_mask_every_nth", "revive_mask_most_activated", "revive_expert_counts",
+           "revive_build_map_experts", "revive_compact_ranks", "revive_mask_every_nth", "revive_mask_most_activated", "revive_expert_counts",
            "revive_route", "revive_dispatch", "revive_expert_ffn", "revive_shared_ffn", "revive_combine",
            "revive_graph_begin", "revive_graph_end", "revive_graph_launch", "revive_graph_exec_id",
            "revive_graph_destroy", "revive_set_kernel_timing", "revive_kernel_time",
@@ -120,6 +121,15 @@ def make_config(cfg, T_max: Optional[int] = None, route_scale: float = 1.0) -> C
                   I_shared=cfg.I_shared, n_ranks=cfg.n_ranks, slots_per_rank=cfg.slots_per_rank,
                   max_replicas=cfg.max_replicas, score_fn=SCORE_FN[cfg.score_fn], n_group=cfg.n_group,
                   topk_group=cfg.topk_group, dtype=DTYPE[cfg.dtype], route_scale=route_scale)
+
+
+def compact_ranks(logical_rank, failed_device: int, switched_device: int = -1) -> np.ndarray:
+    """revive_compact_ranks on a copy of logical_rank (int32[n]); raises on bad input."""
+    r = np.array(logical_rank, dtype=np.int32)
+    rc = lib().revive_compact_ranks(r.ctypes.data, r.shape[0], failed_device, switched_device)
+    if rc != 0:
+        raise ReviveError(rc, lib().revive_last_error(None).decode())
+    return r
 
 
 def mask_every_nth(E: int, n: int) -> np.ndarray:

@@ -299,6 +299,23 @@ int revive_build_map(const revive_config* cfg, const int32_t* phys_to_logical, c
   return revive_build_map_experts(cfg, phys_to_logical, rank_failed, nullptr, l2p_table, l2p_count, slot_alive, stats);
 }
 
+int revive_compact_ranks(int32_t* logical_rank, int32_t n, int32_t failed_device, int32_t switched_device) {
+  if (!logical_rank || n <= 0 || failed_device < 0 || failed_device >= n || switched_device >= n || switched_device == failed_device)
+    return fail(nullptr, REVIVE_EINVAL, "revive_compact_ranks: bad argument");
+  int gap = logical_rank[failed_device];
+  if (gap < 0) return fail(nullptr, REVIVE_EINVAL, "revive_compact_ranks: device %d holds no rank", failed_device);
+  logical_rank[failed_device] = -1;
+  if (switched_device >= 0) {  // the switched device moves into the hole and leaves its own behind
+    const int old = logical_rank[switched_device];
+    logical_rank[switched_device] = gap;
+    gap = old;
+  }
+  if (gap >= 0)
+    for (int d = 0; d < n; ++d)
+      if (logical_rank[d] > gap) --logical_rank[d];
+  return REVIVE_OK;
+}
+
 int revive_mask_every_nth(int32_t E, int32_t n, uint8_t* mask) {
   if (E <= 0 || n <= 0 || !mask) return fail(nullptr, REVIVE_EINVAL, "revive_mask_every_nth: bad argument");
   for (int e = 0; e < E; ++e) mask[e] = e % n == 0;

@@ -125,3 +125,23 @@ def test_host_map_build_with_failed_experts_matches_oracle():
     bad[3] = 7
     cfg = synth.get_config("c1")
     assert pk.build_map_host(cfg, synth.make_placement(cfg), synth.failed_mask(cfg, []), expert_failed=bad)[0] == -1
+
+
+def test_compact_ranks_matches_oracle():
+    pk = _pk()
+    rng = np.random.default_rng(13)
+    for _ in range(100):
+        n = int(rng.integers(2, 16))
+        live = [d for d in range(n) if rng.random() > 0.2]
+        if len(live) < 2:
+            continue
+        ranks = [-1] * n
+        for i, d in enumerate(rng.permutation(live)):
+            ranks[d] = i
+        f = int(rng.choice(live))
+        sw = int(rng.integers(-1, n))
+        if sw == f:
+            sw = -1
+        assert pk.compact_ranks(ranks, f, sw).tolist() == orc.compact_ranks(ranks, f, sw)
+    with pytest.raises(pk.ReviveError):
+        pk.compact_ranks([0, -1, 1], 1)

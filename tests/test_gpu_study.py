@@ -116,3 +116,40 @@ def test_task_based_mask_from_gpu_activation_counts():
             assert np.abs(f64(top_w).sum(axis=1) - 1).max() < 1e-6
     finally:
         g.close()
+
+
+def test_dense_ffn_group_rebalancing_on_the_gpu():
+    """Sec. 3.4, dense FFN layers: one FFN replicated over G groups; when groups are compromised
+    the tokens are spread evenly over the healthy ones.  Through the same map: one logical expert,
+    one replica per group, k = 1, replica t mod (healthy groups)."""
+    import paper_2602_21140_amd as pk
+    G, T, H, I = 6, 1000, 512, 320
+    cfg = synth.LayerConfig("dense_groups", T=T, H=H, E=1, k=1, I=I, I_shared=0, n_ranks=G, slots_per_rank=1,
+                            max_replicas=G, score_fn="softmax", n_group=1, topk_group=1, dtype="bf16", failed_ranks=(1, 4))
+    L = pk.ReviveLayer(cfg)
+    try:
+        p2l = np.zeros(G, dtype=np.int32)
+        L.set_placement(p2l)
+        failed = synth.failed_mask(cfg)
+        stats = L.update_map(failed)
+        assert stats["n_live_slots"] == 4 and stats["n_lost_experts"] == 0
+        x = synth.draw_x(cfg, "cuda:0")
+        w_r = pk.pack_router(synth.draw_router(cfg, "cuda:0"))
+        w = synth.draw_expert(cfg, 0, "cuda:0")
+        gu, dn = pk.pack_expert(w["gate"], w["up"], w["down"])
+        nan = torch.full_like(gu, float("nan")), torch.full_like(dn, float("nan"))
+        gus = [gu.clone() if not failed[p] else nan[0] for p in range(G)]
+        dns = [dn.clone() if not failed[p] else nan[1] for p in range(G)]
+        L.set_expert_weights(gus, dns)
+        lg, top_l, top_w, top_p = L.route(x, w_r, T)
+        x_perm, offs, dst, src = L.dispatch(x, top_p, T)
+        y_perm, _ = L.expert_ffn(x_perm, offs, T, shared=False)
+        out = L.combine(y_perm, dst, top_w, None, T)
+        m = orc.build_map(p2l, failed, 1, 1, G)
+        assert np.array_equal(_i(top_p).ravel(), m.l2p_table[0, np.arange(T) % 4])
+        counts = np.diff(_i(offs))
+        assert counts.tolist() == [250, 0, 250, 250, 0, 250]
+        ref = orc.swiglu_ffn(f64(x), f64(w["gate"]), f64(w["up"]), f64(w["down"]))
+        assert rel_err(f64(out), ref) < TOL["bf16"]
+    finally:
+        L.close()

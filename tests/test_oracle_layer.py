@@ -139,3 +139,22 @@ def test_selection_gap():
     assert orc.selection_gap(row, [0, 2], [0, 2]) == 0.0
     assert orc.selection_gap(row, [0, 2], [0, 1]) == pytest.approx(1e-7)
     assert orc.selection_gap(row, [0, 2], [0, 3]) > 0.29
+
+
+def test_dense_ffn_group_rebalancing_is_the_same_remap():
+    """Sec. 3.4 (last paragraph): a dense FFN replicated over several groups; tokens are spread
+    evenly over the healthy groups.  One logical 'expert' with one replica per group, k = 1."""
+    G, T, H, I = 6, 50, 16, 8
+    r = np.random.default_rng(5)
+    x = r.normal(size=(T, H))
+    w = {"gate": r.normal(size=(H, I)), "up": r.normal(size=(H, I)), "down": r.normal(size=(I, H))}
+    p2l = np.zeros(G, dtype=np.int32)
+    failed = np.zeros(G, np.uint8)
+    failed[[1, 4]] = 1
+    m = orc.build_map(p2l, failed, 1, 1, G)
+    assert m.l2p_table[0, :4].tolist() == [0, 2, 3, 5]
+    tr = orc.layer_staged(x, r.normal(size=(H, 1)), {0: w}, None, p2l, m, 1, "softmax")
+    counts = np.diff(tr.slot_offsets)
+    assert counts[[1, 4]].sum() == 0 and counts[[0, 2, 3, 5]].max() - counts[[0, 2, 3, 5]].min() <= 1
+    assert np.allclose(tr.topk_weight, 1.0)
+    assert np.allclose(tr.out, orc.swiglu_ffn(x, w["gate"], w["up"], w["down"]), atol=1e-12)

@@ -72,3 +72,39 @@ def test_most_activated_mask_properties():
             tied_in = [e for e in range(24) if m[e] and c[e] == worst_in]
             tied_out = [e for e in range(24) if not m[e] and c[e] == worst_in]
             assert not tied_out or max(tied_in) < min(tied_out)
+
+
+def test_rank_compaction_follows_the_papers_description():
+    """Sec. 3.5: device B with rank l_A + 1 takes l_A and later ranks are decremented; with a role
+    switch device C takes l_A and any gap left behind is closed the same way."""
+    assert orc.compact_ranks([0, 1, 2, 3, 4], 2) == [0, 1, -1, 2, 3]
+    assert orc.compact_ranks([0, 1, 2, 3, 4], 4) == [0, 1, 2, 3, -1]
+    assert orc.compact_ranks([0, 1, 2, 3, 4], 0) == [-1, 0, 1, 2, 3]
+    # a device from outside the domain (an attention device) is switched in: nobody else moves
+    assert orc.compact_ranks([0, 1, 2, 3, -1], 1, 4) == [0, -1, 2, 3, 1]
+    # a device of the domain is switched: it takes the hole, the hole it leaves is closed
+    assert orc.compact_ranks([0, 1, 2, 3, 4], 2, 4) == [0, 1, -1, 3, 2]
+    assert orc.compact_ranks([0, 1, 2, 3, 4], 3, 0) == [2, 0, 1, -1, 3]
+    r = np.random.default_rng(4)
+    for _ in range(50):
+        n = int(r.integers(2, 12))
+        ranks = list(r.permutation(n))
+        out_of_domain = r.random(n) < 0.2
+        live = [d for d in range(n) if not out_of_domain[d]]
+        if len(live) < 2:
+            continue
+        ranks = [-1] * n
+        for i, d in enumerate(r.permutation(live)):
+            ranks[d] = i
+        f = int(r.choice(live))
+        sw = int(r.integers(-1, n))
+        if sw == f:
+            sw = -1
+        new = orc.compact_ranks(ranks, f, sw)
+        members = [d for d in range(n) if new[d] >= 0]
+        assert sorted(new[d] for d in members) == list(range(len(members)))     # compact: 0..m-1
+        assert new[f] == -1
+        others = [d for d in members if d != sw]
+        assert sorted(others, key=lambda d: ranks[d]) == sorted(others, key=lambda d: new[d])   # order kept
+        if sw >= 0 and ranks[sw] < 0:
+            assert new[sw] == ranks[f] and all(new[d] == ranks[d] for d in others)
