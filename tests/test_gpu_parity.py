@@ -32,6 +32,11 @@ SMALL = {
     "c3s": _small("c3", T=900, H=512, I=256, I_shared=256),
     "c4s": _small("c4", T=900, H=512, I=256, I_shared=256),
     "c5s": _small("c5", T=1100, H=448, I=192, I_shared=128),
+    # shortest reduction dimensions the bf16 GEMM accepts (2 and 4 K-steps of 32): pipeline prologue and tail only
+    "k64": _small("c2", T=700, H=64, I=64, I_shared=64, E=16, k=2, n_ranks=4, slots_per_rank=5, failed_ranks=(1,),
+                  n_unprotected=-1),
+    "k128": _small("c2", T=600, H=128, I=64, I_shared=128, E=16, k=3, n_ranks=4, slots_per_rank=5, failed_ranks=(),
+                   n_unprotected=-1),
 }
 
 
@@ -161,6 +166,29 @@ def test_no_failure_and_pure_remap_outputs():
         err = rel_err(f64(r["out"]), f64(out0))
         print(f"pure remap: bit-identical={same}, rel diff={err:.2e}")
         assert err < 1e-6 if not same else True
+    finally:
+        g.close()
+
+
+def test_fewer_tokens_than_the_context_was_sized_for():
+    """A context created for T_max tokens serves any T <= T_max (decode batches shrink and grow)."""
+    cfg = SMALL["c2m"]
+    g = GpuLayer(cfg)
+    try:
+        experts = _experts_f64(g)
+        for T in (cfg.T, 257, 64, 1, cfg.T):
+            L = g.layer
+            lg, top_l, top_w, top_p = L.route(g.x, g.w_router_packed, T)
+            x_perm, offs, dst, src = L.dispatch(g.x, top_p, T)
+            y_perm, y_sh = L.expert_ffn(x_perm, offs, T, x=g.x, w_sh_gate_up=g.sh_gate_up, w_sh_down=g.sh_down)
+            out = L.combine(y_perm, dst, top_w, y_sh, T)
+            tr = orc.layer_staged(f64(g.x[:T]), None, experts, g.shared_f64(), g.p2l, g.oracle_map(), cfg.k,
+                                  cfg.score_fn, cfg.n_group, cfg.topk_group, logits=f64(lg))
+            assert np.array_equal(_i(top_p), tr.topk_phys) and np.array_equal(_i(dst), tr.dst_row)
+            assert _i(offs)[-1] == T * cfg.k
+            assert rel_err(f64(out), tr.out) < TOL[cfg.dtype], T
+        with pytest.raises(Exception):
+            g.layer.route(g.x, g.w_router_packed, cfg.T + 1)
     finally:
         g.close()
 
