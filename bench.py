@@ -54,17 +54,16 @@ def cpu_baseline(cfg, g, sample_tokens):
 
     x = f64(g.x[:sample_tokens])
     w_r = f64(g.w_router)
+    from paper_2602_21140_amd import unpack_expert
+
+    def math(gu, dn, I):
+        return {n: np.ascontiguousarray(f64(t)) for n, t in zip(("gate", "up", "down"), unpack_expert(gu, dn, cfg.H, I))}
+
     experts = {}
     for e in range(cfg.E):
         p = int(np.nonzero(g.p2l == e)[0][0])
-        gu = f64(g.gu[p])
-        experts[e] = {"gate": np.ascontiguousarray(gu[:cfg.I].T), "up": np.ascontiguousarray(gu[cfg.I:].T),
-                      "down": np.ascontiguousarray(f64(g.dn[p]).T)}
-    shared = None
-    if g.sh_gate_up is not None:
-        gu = f64(g.sh_gate_up)
-        shared = {"gate": np.ascontiguousarray(gu[:cfg.I_shared].T), "up": np.ascontiguousarray(gu[cfg.I_shared:].T),
-                  "down": np.ascontiguousarray(f64(g.sh_down).T)}
+        experts[e] = math(g.gu[p], g.dn[p], cfg.I)
+    shared = math(g.sh_gate_up, g.sh_down, cfg.I_shared) if g.sh_gate_up is not None else None
     emap = orc.build_map(g.p2l, g.failed, cfg.slots_per_rank, cfg.E, cfg.max_replicas)
     t0 = time.perf_counter()
     orc.layer_staged(x, w_r, experts, shared, g.p2l, emap, cfg.k, cfg.score_fn, cfg.n_group, cfg.topk_group)

@@ -36,11 +36,21 @@
  *   - Element type `dtype`: 0 = fp32, 1 = bf16.  It is the type of x, of all
  *     weights and of x_perm / y_perm / y_shared / out.  Products accumulate in
  *     fp32; bf16 results are rounded to nearest-even once per stored tensor.
- *   - Matrices are row-major.  Weights are stored "output-major":
+ *   - Matrices are row-major.  Weights are "output-major", i.e. the transposes
+ *     of the matrices in y = (silu(x G) * (x U)) D:
  *       w_router      [E, H]      row e  = router column of expert e
- *       w_gate_up[p]  [2*I, H]    rows 0..I-1 gate, rows I..2I-1 up
- *       w_down[p]     [H, I]      row h  = the I weights producing output h
- *     i.e. the transposes of the matrices in y = (silu(x G) * (x U)) D.
+ *       gate / up     [I, H]      row i  = the H weights producing intermediate i
+ *       down          [H, I]      row h  = the I weights producing output h
+ *     fp32 layers take them plainly: w_gate_up[p] = [gate; up] as [2I, H],
+ *     w_down[p] = [H, I].  bf16 layers take gate, up and down in a TILED layout
+ *     that makes every block a workgroup fetches contiguous in HBM: a [rows, K]
+ *     matrix is stored as [ceil(rows/128)][K/32][128][32] elements (rows
+ *     zero-padded to a multiple of 128; element (r, k) sits at
+ *     ((r/128 * K/32 + k/32) * 128 + r%128) * 32 + k%32).  w_gate_up[p] is the
+ *     tiled gate matrix followed by the tiled up matrix; w_down[p] the tiled
+ *     down matrix; the shared expert's matrices likewise.  The router matrix is
+ *     always plain.  The Python binding's pack_expert / unpack_expert convert
+ *     from and to the math layout.
  *   - Limits: E <= 512, P = n_ranks*slots_per_rank <= 1024, k <= 32,
  *     H % 8 == 0; for bf16 additionally H % 64 == 0, I % 64 == 0 and
  *     I_shared % 64 == 0.
@@ -222,11 +232,12 @@ int revive_dispatch(revive_ctx* ctx, const void* x, const int32_t* topk_phys, in
 /* a8 - Expert FFN (Sec. 2.1): for every slot p with rows [slot_offsets[p],
  * slot_offsets[p+1]):  y = (silu(X G_p) * (X U_p)) D_p, and the same on all T
  * rows of x for the shared expert when y_shared != NULL.
- *   w_gate_up  dev table of P dev pointers, entry p -> [2I, H] dtype
- *   w_down     dev table of P dev pointers, entry p -> [H, I]  dtype
+ *   w_gate_up  dev table of P dev pointers, entry p -> gate and up matrices of slot p
+ *   w_down     dev table of P dev pointers, entry p -> down matrix of slot p
+ *              (layouts: see the conventions at the top)
  *              entries of slots that receive no rows are never dereferenced.
  *   y_perm     dev [N, H] dtype
- *   x, w_sh_gate_up [2*I_shared, H], w_sh_down [H, I_shared], y_shared [T, H]:
+ *   x, w_sh_gate_up, w_sh_down (same layouts, width I_shared), y_shared [T, H]:
  *              shared expert; all four may be NULL when I_shared == 0 or the
  *              caller skips it.
  * The intermediate activation is rounded to dtype once. */

@@ -5,7 +5,7 @@ runs in that library's HIP kernels.  Importing this package does not load the li
 a `ReviveLayer` (or calling `binding.lib()`) does, and fails loudly when it has not been built.
 """
 from .binding import (ReviveError, ReviveLayer, build_map_host, compact_ranks, lib, lib_path, mask_every_nth,
-                      mask_most_activated, pack_expert, pack_router, KERNEL_NAMES)
+                      mask_most_activated, pack_expert, pack_router, unpack_expert, KERNEL_NAMES)
 
 __all__ = ["ReviveError", "ReviveLayer", "build_map_host", "compact_ranks", "lib", "lib_path", "mask_every_nth",
-           "mask_most_activated", "pack_expert", "pack_router", "KERNEL_NAMES"]
+           "mask_most_activated", "pack_expert", "pack_router", "unpack_expert", "KERNEL_NAMES"]

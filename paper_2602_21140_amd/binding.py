@@ -176,10 +176,47 @@ def pack_router(w_router: torch.Tensor) -> torch.Tensor:
     return w_router.t().contiguous()
 
 
+TILE_ROWS, TILE_K = 128, 32   # tiled weight layout of bf16 layers (include/revive.h)
+
+
+def _tile(w: torch.Tensor) -> torch.Tensor:
+    """[rows, K] -> the tiled layout [ceil(rows/128)*128, K] (same storage order as
+    [rows/128][K/32][128][32]); rows zero-padded to a multiple of 128."""
+    rows, K = w.shape
+    assert K % TILE_K == 0
+    pad = -rows % TILE_ROWS
+    if pad:
+        w = torch.cat([w, w.new_zeros(pad, K)], dim=0)
+    rp = rows + pad
+    return w.reshape(rp // TILE_ROWS, TILE_ROWS, K // TILE_K, TILE_K).permute(0, 2, 1, 3).contiguous().reshape(rp, K)
+
+
+def _untile(t: torch.Tensor, rows: int) -> torch.Tensor:
+    rp, K = t.shape
+    w = t.reshape(rp // TILE_ROWS, K // TILE_K, TILE_ROWS, TILE_K).permute(0, 2, 1, 3).reshape(rp, K)
+    return w[:rows]
+
+
+def padded_rows(rows: int) -> int:
+    return rows + (-rows % TILE_ROWS)
+
+
 def pack_expert(gate: torch.Tensor, up: torch.Tensor, down: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
-    """Math-layout expert matrices (gate/up [H, I], down [I, H]) -> the library's layouts:
-    w_gate_up [2I, H] (gate rows, then up rows) and w_down [H, I]."""
+    """Math-layout expert matrices (gate/up [H, I], down [I, H]) -> the library's layouts.
+
+    fp32: w_gate_up = [gate^T; up^T] as [2I, H], w_down = down^T as [H, I].
+    bf16: the same matrices in the tiled layout (each of gate^T, up^T, down^T tiled separately)."""
+    if gate.dtype == torch.bfloat16:
+        return torch.cat([_tile(gate.t()), _tile(up.t())], dim=0).contiguous(), _tile(down.t())
     return torch.cat([gate.t(), up.t()], dim=0).contiguous(), down.t().contiguous()
+
+
+def unpack_expert(w_gate_up: torch.Tensor, w_down: torch.Tensor, H: int, I: int):
+    """Inverse of pack_expert: (gate [H, I], up [H, I], down [I, H])."""
+    if w_gate_up.dtype == torch.bfloat16:
+        ip = padded_rows(I)
+        return (_untile(w_gate_up[:ip], I).t(), _untile(w_gate_up[ip:], I).t(), _untile(w_down, H).t())
+    return w_gate_up[:I].t(), w_gate_up[I:].t(), w_down.t()
 
 
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
@@ -282,8 +319,11 @@ class ReviveLayer:
         assert len(w_gate_up) == self.P and len(w_down) == self.P
         for gu, dn in zip(w_gate_up, w_down):
             if gu is not None:
-                assert gu.shape == (2 * self.cfg.I, self.cfg.H) and gu.dtype == self.dtype and gu.is_contiguous()
-                assert dn.shape == (self.cfg.H, self.cfg.I) and dn.dtype == self.dtype and dn.is_contiguous()
+                tiled = self.dtype == torch.bfloat16
+                gu_rows = 2 * (padded_rows(self.cfg.I) if tiled else self.cfg.I)
+                dn_rows = padded_rows(self.cfg.H) if tiled else self.cfg.H
+                assert gu.shape == (gu_rows, self.cfg.H) and gu.dtype == self.dtype and gu.is_contiguous()
+                assert dn.shape == (dn_rows, self.cfg.I) and dn.dtype == self.dtype and dn.is_contiguous()
         self._w_keep = (list(w_gate_up), list(w_down))
         gu_tab = torch.tensor([0 if t is None else t.data_ptr() for t in w_gate_up], dtype=torch.int64)
         dn_tab = torch.tensor([0 if t is None else t.data_ptr() for t in w_down], dtype=torch.int64)

@@ -87,6 +87,8 @@ GemmArgs gate_up_args(const revive_ctx* ctx, const Bf16Ffn& f, int bn_out) {
   a.tiles = f.tiles; a.tile_count = f.tile_count; a.M = f.M;
   a.n_col_tiles = ceil_div(f.I, bn_out);
   a.b_sel = f.tiles ? 0 : -1;
+  a.b_tiled = 1;
+  a.b_rows_pad = ceil_div(f.I, kWeightTileRows) * kWeightTileRows;
   return a;
 }
 
@@ -99,6 +101,8 @@ GemmArgs down_args(const revive_ctx* ctx, const Bf16Ffn& f, int bn_out) {
   d.tiles = f.tiles; d.tile_count = f.tile_count; d.M = f.M;
   d.n_col_tiles = ceil_div(ctx->cfg.H, bn_out);
   d.b_sel = f.tiles ? 1 : -1;
+  d.b_tiled = 1;
+  d.b_rows_pad = ceil_div(ctx->cfg.H, kWeightTileRows) * kWeightTileRows;
   return d;
 }
 

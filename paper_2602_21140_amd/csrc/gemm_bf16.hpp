@@ -42,6 +42,12 @@ __device__ __forceinline__ u32x4 load_global_16B(const unsigned char* p) {
 
 enum { EPI_F32 = 0, EPI_BF16 = 1, EPI_SWIGLU = 2 };
 
+// Tiled weight layout: a [rows, K] output-major matrix is stored as [rows/128][K/32][128][32]
+// (rows zero-padded to a multiple of 128), so the 128 x 32 block a workgroup fetches per K-step is
+// 8 KiB contiguous and a whole 128-row panel is one contiguous stream over K.
+constexpr int kWeightTileRows = 128;
+constexpr int kWeightTileK = 32;
+
 struct GemmArgs {
   const void* A;             // [rows, K] bf16
   int64_t lda;               // elements between rows of A
@@ -57,6 +63,8 @@ struct GemmArgs {
   int M;                     // dense case: number of rows
   int n_col_tiles;
   int b_sel;                 // -1: weights from B_tab / B_one; 0 or 1: from the tile record's w[b_sel]
+  int b_tiled;               // B is stored in the tiled weight layout (see kWeightTileRows)
+  int b_rows_pad;            // tiled: rows of B (of each half for SwiGLU) padded to whole tiles
 };
 
 // Up to two independent problems served by one launch (e.g. the routed experts' grouped GEMM and
@@ -375,7 +383,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   const int n0 = n_idx * BN_OUT;
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform: keeps per-wavefront offsets in SGPRs
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
   // ---- copy plan: instruction i of this wavefront fills rows [(wave*CP_x + i)*16, +16) of the A
@@ -393,15 +402,28 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
       cp_src[i] = Abase + (static_cast<int64_t>(grow) * g.lda + chunk * 8) * 2;
       cp_dst[i] = blk * 1024;
     } else {
-      int brow;
-      if (EPI == EPI_SWIGLU) {
-        const int half = row >= BN / 2;
-        const int col = min(n0 + row - half * (BN / 2), g.n_out - 1);
-        brow = col + half * g.n_out;
+      if (g.b_tiled) {
+        // padded row index of this LDS row in the tiled matrix (gate half first, then up half)
+        int R;
+        if (EPI == EPI_SWIGLU) {
+          const int half = row >= BN / 2;
+          R = min(n0 + row - half * (BN / 2), g.b_rows_pad - 1) + half * g.b_rows_pad;
+        } else {
+          R = min(n0 + row, g.b_rows_pad - 1);
+        }
+        const int64_t panel = static_cast<int64_t>(R / kWeightTileRows) * (g.K / kWeightTileK) * kWeightTileRows;
+        cp_src[i] = Bbase + ((panel + (R % kWeightTileRows)) * kWeightTileK + chunk * 8) * 2;
       } else {
-        brow = min(n0 + row, g.n_out - 1);
+        int brow;
+        if (EPI == EPI_SWIGLU) {
+          const int half = row >= BN / 2;
+          const int col = min(n0 + row - half * (BN / 2), g.n_out - 1);
+          brow = col + half * g.n_out;
+        } else {
+          brow = min(n0 + row, g.n_out - 1);
+        }
+        cp_src[i] = Bbase + (static_cast<int64_t>(brow) * g.ldb + chunk * 8) * 2;
       }
-      cp_src[i] = Bbase + (static_cast<int64_t>(brow) * g.ldb + chunk * 8) * 2;
       cp_dst[i] = BM * 64 + blk * 1024;
     }
   }
@@ -412,32 +434,34 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   const uint32_t smem_lds = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lptr)smem));
   auto issue_copy = [&](int kt) {
     const uint32_t stage = smem_lds + stage_of(kt) * STAGE;
-    const int64_t koff = static_cast<int64_t>(kt) * 64;  // 32 bf16
+    const int64_t koff_a = static_cast<int64_t>(kt) * 64;  // 32 bf16 further along the row
+    const int64_t koff_b = g.b_tiled ? static_cast<int64_t>(kt) * (kWeightTileRows * kWeightTileK * 2) : koff_a;
 #pragma unroll
     for (int i = 0; i < CP; ++i) {
-      const unsigned char* src = cp_src[i] + koff;
+      const unsigned char* src = cp_src[i] + (i < CP_A ? koff_a : koff_b);
       const uint32_t dst = __builtin_amdgcn_readfirstlane(stage + cp_dst[i]);
       asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(dst) : "memory", "m0");
     }
   };
 
-  // ---- per-lane fragment rows
-  int a_frag[TM], b_frag[TN];
-  // 32-row sub-tiles are dealt round-robin to the wavefront rows (sub-tile tm*WAVES_M + wm), so a
-  // ragged row-tile keeps every wavefront equally busy.
+  // ---- per-lane fragment addresses.  32-row sub-tiles are dealt round-robin to the wavefront
+  // rows (sub-tile tm*WAVES_M + wm), so a ragged row-tile keeps every wavefront equally busy.
+  // Every fragment row of a lane is (a multiple of 32) + lane % 32, so the swizzle term depends on
+  // the lane only: the lane keeps one loop-invariant byte offset per operand and half-step, and
+  // the individual fragments are reached with immediate offsets from it.
+  const int lrow = lane & 31;
+  int a_off[2], b_off[2];
 #pragma unroll
-  for (int tm = 0; tm < TM; ++tm) a_frag[tm] = (tm * WAVES_M + wm) * 32 + (lane & 31);
-#pragma unroll
-  for (int tn = 0; tn < TN; ++tn) {
-    int r;
-    if (EPI == EPI_SWIGLU) {
-      const int half = tn >= TN / 2;
-      r = half * (BN / 2) + wn * (WN / 2) + (tn - half * (TN / 2)) * 32 + (lane & 31);
-    } else {
-      r = wn * WN + tn * 32 + (lane & 31);
-    }
-    b_frag[tn] = BM + r;
+  for (int ks = 0; ks < 2; ++ks) {
+    const int sw = ((ks * 2 + (lane >> 5)) ^ swz32(lrow)) << 4;
+    a_off[ks] = (wm * 32 + lrow) * 64 + sw;
+    b_off[ks] = (BM + (EPI == EPI_SWIGLU ? wn * (WN / 2) : wn * WN) + lrow) * 64 + sw;
   }
+  constexpr int A_STEP = WAVES_M * 32 * 64;  // bytes between a wavefront's successive row sub-tiles
+  auto b_imm = [](int tn) {                   // byte offset of column tile tn from the lane's base
+    if (EPI == EPI_SWIGLU) return ((tn >= TN / 2 ? BN / 2 : 0) + (tn % (TN / 2 > 0 ? TN / 2 : 1)) * 32) * 64;
+    return tn * 32 * 64;
+  };
   f32x16 acc[TM][TN];
 #pragma unroll
   for (int tm = 0; tm < TM; ++tm)
@@ -457,17 +481,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
     constexpr int TMV = decltype(tmv_tag)::value;
     auto load_frags = [&](const unsigned char* base, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
       if (TMV == 0) return;
-      const int chunk = ks * 2 + (lane >> 5);
+      const unsigned char* pa = base + a_off[ks];
+      const unsigned char* pb = base + b_off[ks];
 #pragma unroll
-      for (int tm = 0; tm < TMV; ++tm) {
-        const int r = a_frag[tm];
-        af[tm] = *reinterpret_cast<const bf16x8*>(base + r * 64 + ((chunk ^ swz32(r)) << 4));
-      }
+      for (int tm = 0; tm < TMV; ++tm) af[tm] = *reinterpret_cast<const bf16x8*>(pa + tm * A_STEP);
 #pragma unroll
-      for (int tn = 0; tn < TN; ++tn) {
-        const int r = b_frag[tn];
-        bfr[tn] = *reinterpret_cast<const bf16x8*>(base + r * 64 + ((chunk ^ swz32(r)) << 4));
-      }
+      for (int tn = 0; tn < TN; ++tn) bfr[tn] = *reinterpret_cast<const bf16x8*>(pb + b_imm(tn));
     };
     auto mfma_step = [&](const bf16x8 (&af)[TM], const bf16x8 (&bfr)[TN]) {
 #pragma unroll

@@ -34,24 +34,23 @@ class GpuLayer(ResidentLayer):
         return orc.build_map(self.p2l, self.failed, c.slots_per_rank, c.E, c.max_replicas,
                              expert_failed=self.expert_failed)
 
+    def _math_f64(self, gu, dn, I) -> Dict[str, np.ndarray]:
+        from paper_2602_21140_amd import unpack_expert
+        g, u, d = unpack_expert(gu, dn, self.cfg.H, I)
+        return {"gate": f64(g), "up": f64(u), "down": f64(d)}
+
     def expert_f64(self, e: int) -> Dict[str, np.ndarray]:
         """Expert e's matrices in math layout, fp64, read back from the first slot that holds it."""
         p = int(np.nonzero(self.p2l == e)[0][0])
-        I = self.cfg.I
-        gu = f64(self.gu[p])
-        return {"gate": gu[:I].T, "up": gu[I:].T, "down": f64(self.dn[p]).T}
+        return self._math_f64(self.gu[p], self.dn[p], self.cfg.I)
 
     def slot_expert_f64(self, p: int) -> Dict[str, np.ndarray]:
-        I = self.cfg.I
-        gu = f64(self.gu[p])
-        return {"gate": gu[:I].T, "up": gu[I:].T, "down": f64(self.dn[p]).T}
+        return self._math_f64(self.gu[p], self.dn[p], self.cfg.I)
 
     def shared_f64(self) -> Optional[Dict[str, np.ndarray]]:
         if self.sh_gate_up is None:
             return None
-        Is = self.cfg.I_shared
-        gu = f64(self.sh_gate_up)
-        return {"gate": gu[:Is].T, "up": gu[Is:].T, "down": f64(self.sh_down).T}
+        return self._math_f64(self.sh_gate_up, self.sh_down, self.cfg.I_shared)
 
 
 def compare_selection(cfg, gpu_top: np.ndarray, sel: np.ndarray, ref_top: np.ndarray, gap_limit=1e-5):
