@@ -43,6 +43,37 @@ def algorithmic_work(cfg):
     }
 
 
+DOMINANT_KERNEL_SOURCES = ("gemm_bf16.hpp", "ffn.hip", "ctx.hpp")
+
+
+def kernel_source_hash():
+    """SHA-256 over the sources of the dominant kernel, the key that ties stored counters to a kernel version."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in DOMINANT_KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2602_21140_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def stored_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed counter summary of this workload, or None
+    when there is none or the kernel's sources have changed since the counters were collected."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_ffn_gate_up_hbm_traffic.txt")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    fields = dict(line.split("=", 1) for line in text.splitlines() if "=" in line and not line.startswith(" "))
+    fields = {k.strip(): v.strip() for k, v in fields.items()}
+    if fields.get("kernel_sources_sha256") != kernel_source_hash():
+        return None
+    try:
+        return float(fields["traffic_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
 def cpu_baseline(cfg, g, sample_tokens):
     """Time the oracle (as it stands) on the first `sample_tokens` tokens of the workload."""
     import numpy as np
@@ -209,7 +240,7 @@ def main():
                      "achieved": dom_tflops, "peak": peak, "unit": "TFLOP/s", "frac": dom_tflops / peak,
                      "avg_launch_us": avg_us[dom], "flops_per_launch": dom_flops,
                      "launch_covers": "routed experts + shared expert gate/up projections" if merged else "routed experts gate/up projection",
-                     "traffic": None},
+                     "traffic": stored_traffic(cfg.name)},
         "stages": stages,
         "remap": {"update_map_host_ms": host_ms, "update_to_first_step_done_ms": first_ms,
                   "minus_steady_step_ms": first_ms - ms_per_step, "routes_avoid_failed_ranks": all(r[2] for r in remap),
