@@ -9,7 +9,8 @@ from one captured graph.  Prints one JSON line:
   roofline     the dominant kernel (grouped gate/up GEMM of the routed experts) against the bf16
                dense MFMA peak, from HIP-event timing of that kernel inside this run
   cpu_baseline the CPU oracle timed on this host on a bounded sample of the same workload
-  stages       per-kernel mean microseconds and the stage rates (GB/s, TFLOP/s)
+  stages       per-kernel mean microseconds (one HIP-event pair per launch) and the stage rates (GB/s,
+               TFLOP/s) from events recorded between the stages of the same eager step
   remap        latency from revive_update_map to the end of the first step under the new map,
                replaying the same graph executable
 """
@@ -168,6 +169,15 @@ def main():
         times = L.kernel_times()
         L.set_kernel_timing(False)
 
+        # whole stages of the same eager step (one event between stages, no per-kernel events)
+        marks = []
+        for _ in range(K):
+            g.forward(stream=stream, overlap_shared=False, stage_marks=marks)
+        stream.synchronize()
+        stage_us = {}
+        for si, name in enumerate(("route", "dispatch", "expert_ffn", "combine")):
+            stage_us[name] = 1e3 * sum(marks[5 * s + si].elapsed_time(marks[5 * s + si + 1]) for s in range(K)) / K
+
         # recovery: flip the mask, replay the same executable, time to the end of the first new step
         other = [r for r in range(cfg.n_ranks) if r not in cfg.failed_ranks]
         new_failed = list(cfg.failed_ranks[:-1]) + [other[len(other) // 2]] if cfg.failed_ranks else [other[0]]
@@ -205,19 +215,18 @@ def main():
     dom_tflops = dom_flops / (avg_us[dom] * 1e-6) / 1e12
     peak = MFMA_PEAK_TFLOPS[cfg.dtype]
 
-    def gbs(nbytes, names):
-        us = sum(avg_us[n] for n in names if avg_us[n])
-        return nbytes / (us * 1e-6) / 1e9 if us else None
+    def gbs(nbytes, stage):
+        return nbytes / (stage_us[stage] * 1e-6) / 1e9
 
-    ffn_names = ["ffn_tiles", "ffn_gate_up", "ffn_down", "ffn_shared_gate_up", "ffn_shared_down"]
-    ffn_us = sum(avg_us[n] for n in ffn_names if avg_us[n])
+    ffn_us = stage_us["expert_ffn"]
     ffn_flops = sum(work[n] for n in ("gate_up_flops", "down_flops", "shared_gate_up_flops", "shared_down_flops"))
     stages = {
         "kernel_us": {n: (round(v, 2) if v else None) for n, v in avg_us.items()},
-        "route_GBs": gbs(work["route_bytes"], ["router_gemm", "route_topk"]),
-        "dispatch_GBs": gbs(work["dispatch_bytes"], ["dispatch_count", "dispatch_scan", "dispatch_place", "dispatch_permute"]),
+        "stage_us": {n: round(v, 2) for n, v in stage_us.items()},
+        "route_GBs": gbs(work["route_bytes"], "route"),
+        "dispatch_GBs": gbs(work["dispatch_bytes"], "dispatch"),
         "dispatch_frac_of_hbm": None,
-        "combine_GBs": gbs(work["combine_bytes"], ["combine"]),
+        "combine_GBs": gbs(work["combine_bytes"], "combine"),
         "ffn_TFLOPs": ffn_flops / (ffn_us * 1e-6) / 1e12,
         "ffn_frac_of_mfma_peak": ffn_flops / (ffn_us * 1e-6) / 1e12 / peak,
         "sum_kernel_us": round(sum(v for v in avg_us.values() if v), 1),

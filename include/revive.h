@@ -115,7 +115,10 @@ int revive_destroy(revive_ctx* ctx);
 /* Size of the scratch workspace the data-path calls need (block histograms,
  * GEMM tile lists, the FFN's intermediate activations), and binding of a
  * caller-owned device buffer of at least that size (256-byte aligned).  The
- * buffer must stay valid until the context is destroyed or another is bound. */
+ * buffer must stay valid until the context is destroyed or another is bound.
+ * Binding writes a few bytes of the buffer (synchronously); the data-path
+ * calls of one context share the workspace, so calls that overlap in time on
+ * different streams race. */
 int revive_workspace_bytes(const revive_ctx* ctx, size_t* bytes /*host*/);
 int revive_bind_workspace(revive_ctx* ctx, void* dev, size_t bytes);
 
@@ -280,9 +283,7 @@ int revive_graph_destroy(revive_graph* g);
 enum {
   REVIVE_K_ROUTER_GEMM = 0,
   REVIVE_K_ROUTE_TOPK,
-  REVIVE_K_DISPATCH_COUNT,
-  REVIVE_K_DISPATCH_SCAN,
-  REVIVE_K_DISPATCH_PLACE,
+  REVIVE_K_DISPATCH_INDEX,
   REVIVE_K_DISPATCH_PERMUTE,
   REVIVE_K_FFN_TILES,
   REVIVE_K_FFN_GATE_UP,

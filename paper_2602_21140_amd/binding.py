@@ -21,7 +21,7 @@ SCORE_FN = {"softmax": 0, "sigmoid": 1}
 DTYPE = {"fp32": 0, "bf16": 1}
 TORCH_DTYPE = {"fp32": torch.float32, "bf16": torch.bfloat16}
 
-KERNEL_NAMES = ["router_gemm", "route_topk", "dispatch_count", "dispatch_scan", "dispatch_place",
+KERNEL_NAMES = ["router_gemm", "route_topk", "dispatch_index",
                 "dispatch_permute", "ffn_tiles", "ffn_gate_up", "ffn_down", "ffn_shared_gate_up",
                 "ffn_shared_down", "combine", "expert_counts"]
 

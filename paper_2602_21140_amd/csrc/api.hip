@@ -172,6 +172,8 @@ int revive_create(const revive_config* cfg, revive_ctx** out) {
   size_t off = 0;
   w.off_block_hist = off;
   off = align_up(off + sizeof(int32_t) * std::max<int64_t>(1, ceil_div(static_cast<int>(N_max), kDispatchChunk)) * P, 256);
+  w.off_ticket = off;
+  off = align_up(off + sizeof(uint32_t), 256);
   w.off_tiles = off;
   off = align_up(off + sizeof(MTile) * max_tiles(N_max, static_cast<int>(P), tile_m), 256);
   w.off_tile_count = off;
@@ -229,6 +231,8 @@ int revive_bind_workspace(revive_ctx* ctx, void* dev, size_t bytes) {
   if (!ctx || !dev) return fail(ctx, REVIVE_EINVAL, "revive_bind_workspace: null argument");
   if (bytes < ctx->ws.bytes) return fail(ctx, REVIVE_ENOMEM, "revive_bind_workspace: %zu bytes given, %zu needed", bytes, ctx->ws.bytes);
   if (reinterpret_cast<uintptr_t>(dev) % 256 != 0) return fail(ctx, REVIVE_EINVAL, "revive_bind_workspace: buffer must be 256-byte aligned");
+  // the dispatch ticket must start at zero; every launch leaves it at zero again
+  REVIVE_HIP(ctx, hipMemset(static_cast<uint8_t*>(dev) + ctx->ws.off_ticket, 0, sizeof(uint32_t)));
   ctx->d_ws = static_cast<uint8_t*>(dev);
   ctx->ws_bound = bytes;
   return REVIVE_OK;
@@ -515,7 +519,7 @@ int revive_reset_kernel_times(revive_ctx* ctx) {
 
 const char* revive_kernel_name(int32_t kernel) {
   static const char* names[REVIVE_K_COUNT] = {
-      "router_gemm", "route_topk", "dispatch_count", "dispatch_scan", "dispatch_place", "dispatch_permute",
+      "router_gemm", "route_topk", "dispatch_index", "dispatch_permute",
       "ffn_tiles", "ffn_gate_up", "ffn_down", "ffn_shared_gate_up", "ffn_shared_down", "combine", "expert_counts"};
   return kernel >= 0 && kernel < REVIVE_K_COUNT ? names[kernel] : "?";
 }

@@ -46,6 +46,7 @@ struct MapLayout {
 
 struct Workspace {
   size_t off_block_hist;  // int32 [n_chunks_max * P]
+  size_t off_ticket;      // uint32 [1] (+ padding): finished-workgroup counter of the dispatch index kernel, zero between launches
   size_t off_tiles;       // MTile [max_tiles_routed]
   size_t off_tile_count;  // int32 [4]
   size_t off_h;           // dtype [N_max * I]

@@ -5,51 +5,63 @@
 // rank, so the sorted buffer is rank-segmented: segment r is what rank r would receive.  A failed
 // rank's slots never appear in topk_phys (Sec. 3.4), so its segment is empty (Sec. 3.5).
 //
-// Four kernels, all with grids fixed by T:
-//   count    per-chunk LDS histogram of the slot ids               -> block_hist[chunk][P]
-//   scan     column scan over chunks, then exclusive scan over P   -> block_hist (bases), slot_offsets
-//   place    stable rank of every routed row inside its chunk      -> dst_row, src_of
-//   permute  one workgroup per token: read the row once, write it to its k destinations
+// Two kernels, both with grids fixed by T:
+//   index    per-chunk LDS histogram of the slot ids -> block_hist[chunk][P]; the workgroup that
+//            finishes last turns the columns into running sums over the chunks and scans the
+//            totals over P -> block_hist (bases), slot_offsets
+//   permute  one workgroup per token: stable destination of each of its k routed rows (rows of
+//            the same chunk and slot that come before it are counted from topk_phys, which is
+//            L2-resident), then the row is read once and written to its k destinations
 #include "ctx.hpp"
 
 namespace revive {
 
 namespace {
 
-constexpr int kChunk = kDispatchChunk;  // routed rows per workgroup
+constexpr int kChunk = kDispatchChunk;  // routed rows per workgroup of the index kernel
 constexpr int kThreads = 256;
-constexpr int kSteps = kChunk / kThreads;
+static_assert(kMaxK < kChunk, "a token's rows touch at most two chunks");
 
-__global__ __launch_bounds__(kThreads) void dispatch_count_kernel(const int32_t* __restrict__ topk_phys, int N, int P,
-                                                                  int32_t* __restrict__ block_hist) {
+// One workgroup of kMaxP threads per chunk: a thread handles one routed row of the histogram and,
+// in the workgroup that finishes last, one slot column of the scan.
+// `ticket` counts finished workgroups; the last one resets it, so it is zero between launches.
+__global__ __launch_bounds__(kMaxP) void dispatch_index_kernel(const int32_t* __restrict__ topk_phys, int N, int P,
+                                                               int32_t* block_hist, int32_t* __restrict__ slot_offsets,
+                                                               unsigned int* ticket) {
+  static_assert(kChunk == kMaxP, "one routed row and one slot column per thread");
   __shared__ int hist[kMaxP];
-  for (int p = threadIdx.x; p < P; p += kThreads) hist[p] = 0;
+  __shared__ int wave_sums[kMaxP / 64];
+  __shared__ int last_flag;
+  const int p = threadIdx.x;
+  hist[p] = 0;
   __syncthreads();
-  const int base = blockIdx.x * kChunk;
-#pragma unroll
-  for (int s = 0; s < kSteps; ++s) {
-    const int i = base + s * kThreads + threadIdx.x;
-    if (i < N) {
-      const int p = topk_phys[i];
-      if (p >= 0 && p < P) atomicAdd(&hist[p], 1);
-    }
+  const int i = blockIdx.x * kChunk + threadIdx.x;
+  if (i < N) {
+    const int q = topk_phys[i];
+    if (q >= 0 && q < P) atomicAdd(&hist[q], 1);
   }
   __syncthreads();
-  for (int p = threadIdx.x; p < P; p += kThreads) block_hist[static_cast<int64_t>(blockIdx.x) * P + p] = hist[p];
-}
+  if (p < P) block_hist[static_cast<int64_t>(blockIdx.x) * P + p] = hist[p];
 
-// One workgroup of 1024 threads.  Thread p turns column p of block_hist into exclusive running
-// sums over the chunks (the rows of slot p that earlier chunks hold); the totals are then scanned
-// over p.  slot_offsets[P] = number of valid routed rows.
-__global__ __launch_bounds__(kMaxP) void dispatch_scan_kernel(int32_t* __restrict__ block_hist, int n_chunks, int P,
-                                                              int32_t* __restrict__ slot_offsets) {
-  __shared__ int wave_sums[kMaxP / 64];
-  const int p = threadIdx.x;
+  // Publish this chunk's histogram device-wide, then take a ticket; only the workgroup holding the
+  // last ticket goes on (nobody waits for anybody).  The barrier orders the workgroup's stores
+  // before thread 0's release, and thread 0's acquire before the workgroup's later loads; one
+  // thread does the device-scope part because each such fence is a cache operation of its own.
+  // Every wavefront first waits until its own stores have been accepted by L2.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (threadIdx.x == 0)
+    last_flag = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1;
+  __syncthreads();
+  if (!last_flag) return;
+
+  // Column p of block_hist becomes exclusive running sums over the chunks (the rows of slot p that
+  // earlier chunks hold); `run` ends as the column total.
+  const int n_chunks = gridDim.x;
   int run = 0;
   if (p < P) {
-    // eight independent loads in flight per thread, then the dependent running sum
     int b = 0;
-    for (; b + 8 <= n_chunks; b += 8) {
+    for (; b + 8 <= n_chunks; b += 8) {  // eight independent loads in flight, then the dependent sums
       int v[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) v[j] = block_hist[static_cast<int64_t>(b + j) * P + p];
@@ -66,93 +78,79 @@ __global__ __launch_bounds__(kMaxP) void dispatch_scan_kernel(int32_t* __restric
       run += v;
     }
   }
-  // exclusive scan of `run` over the workgroup: wavefront scan, then scan of the wave totals
+  // exclusive scan of `run` over the slots: wavefront scan, then scan of the wavefront totals
   const int lane = p & 63, wave = p >> 6;
   int incl = run;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
-    const int v = __shfl_up(incl, o);
-    if (lane >= o) incl += v;
+    const int u = __shfl_up(incl, o);
+    if (lane >= o) incl += u;
   }
   if (lane == 63) wave_sums[wave] = incl;
   __syncthreads();
   if (wave == 0) {
-    int w = lane < kMaxP / 64 ? wave_sums[lane] : 0;
+    const int w = lane < kMaxP / 64 ? wave_sums[lane] : 0;
     int wi = w;
 #pragma unroll
-    for (int o = 1; o < 16; o <<= 1) {
-      const int v = __shfl_up(wi, o);
-      if (lane >= o) wi += v;
+    for (int o = 1; o < kMaxP / 64; o <<= 1) {
+      const int u = __shfl_up(wi, o);
+      if (lane >= o) wi += u;
     }
     if (lane < kMaxP / 64) wave_sums[lane] = wi - w;
   }
   __syncthreads();
   const int excl = wave_sums[wave] + incl - run;
   if (p < P) slot_offsets[p] = excl;
-  if (p == P - 1) slot_offsets[P] = excl + run;
+  if (p == P - 1) {
+    slot_offsets[P] = excl + run;  // number of valid routed rows
+    *ticket = 0;
+  }
 }
 
-// Stable placement.  Rows of a chunk are visited in ascending index: step s covers rows
-// base + s*256 + [0, 256), wavefront w the 64 rows after base + s*256 + w*64.  Inside a wavefront
-// the lanes holding the same slot are found with one ballot per bit of the slot id; the lowest
-// such lane records the wavefront's count for that slot, counts are prefix-summed over the four
-// wavefronts and carried from step to step in `running`.
-__global__ __launch_bounds__(kThreads) void dispatch_place_kernel(const int32_t* __restrict__ topk_phys, int N, int P, int nbits,
-                                                                  const int32_t* __restrict__ block_base,
-                                                                  const int32_t* __restrict__ slot_offsets,
-                                                                  int32_t* __restrict__ dst_row, int32_t* __restrict__ src_of) {
-  __shared__ int running[kMaxP];
-  __shared__ int wave_cnt[kThreads / 64][kMaxP];
-  for (int p = threadIdx.x; p < P; p += kThreads) {
-    running[p] = slot_offsets[p] + block_base[static_cast<int64_t>(blockIdx.x) * P + p];
-#pragma unroll
-    for (int w = 0; w < kThreads / 64; ++w) wave_cnt[w][p] = 0;
+// One workgroup per token; 16-byte words.  Routed row i = t*k + j goes to
+//   slot_offsets[p] + (rows of slot p in earlier chunks) + (rows of slot p earlier in i's chunk),
+// the position a stable counting sort by slot gives it.
+__global__ __launch_bounds__(kThreads) void dispatch_permute_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ topk_phys,
+                                                                    int k, int P, const int32_t* __restrict__ block_base,
+                                                                    const int32_t* __restrict__ slot_offsets, int row_words,
+                                                                    int32_t* __restrict__ dst_row, int32_t* __restrict__ src_of,
+                                                                    uint4* __restrict__ x_perm) {
+  __shared__ int slot[kMaxK], cnt[kMaxK], dst[kMaxK];
+  const int t = blockIdx.x;
+  const int i0 = t * k;
+  if (threadIdx.x < k) {
+    int p = topk_phys[i0 + threadIdx.x];
+    if (p < 0 || p >= P) p = -1;  // slot id outside [0, P): the row is dropped
+    slot[threadIdx.x] = p;
+    cnt[threadIdx.x] = 0;
   }
   __syncthreads();
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int base = blockIdx.x * kChunk;
-  for (int s = 0; s < kSteps; ++s) {
-    const int i = base + s * kThreads + threadIdx.x;
-    int p = -1;
-    if (i < N) {
-      p = topk_phys[i];
-      if (p < 0 || p >= P) p = -1;
+  const int lane = threadIdx.x & 63;
+  const int first = (i0 / kChunk) * kChunk;  // start of the chunk that holds row i0
+  const int last_row = i0 + k - 1;
+  for (int b = first; b < last_row; b += kThreads) {
+    const int idx = b + threadIdx.x;
+    const int v = idx < last_row ? topk_phys[idx] : -1;
+    for (int j = 0; j < k; ++j) {
+      const int ij = i0 + j;
+      const int start_j = (ij / kChunk) * kChunk;
+      const bool hit = v >= 0 && v == slot[j] && idx >= start_j && idx < ij;
+      const unsigned long long m = __ballot(hit);
+      if (lane == 0 && m) atomicAdd(&cnt[j], __popcll(m));
     }
-    const bool valid = p >= 0;
-    unsigned long long peers = __ballot(valid);
-    for (int b = 0; b < nbits; ++b) {
-      const bool bit = (p >> b) & 1;
-      const unsigned long long m = __ballot(valid && bit);
-      peers &= bit ? m : ~m;
-    }
-    const unsigned long long below = peers & ((1ull << lane) - 1ull);
-    const int rank = __popcll(below);
-    const bool leader = valid && below == 0;
-    if (leader) wave_cnt[wave][p] = __popcll(peers);
-    __syncthreads();
-    if (valid) {
-      int at = running[p] + rank;
-      for (int w = 0; w < wave; ++w) at += wave_cnt[w][p];
-      dst_row[i] = at;
-      src_of[at] = i;
-    } else if (i < N) {
-      dst_row[i] = -1;  // slot id outside [0, P): the row is dropped
-    }
-    __syncthreads();
-    if (leader) {
-      atomicAdd(&running[p], __popcll(peers));
-      wave_cnt[wave][p] = 0;
-    }
-    __syncthreads();
   }
-}
-
-// One workgroup per token; 16-byte words.  The row is read once and written k times.
-__global__ __launch_bounds__(kThreads) void dispatch_permute_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ dst_row,
-                                                                    int k, int row_words, uint4* __restrict__ x_perm) {
-  __shared__ int dst[kMaxK];
-  const int t = blockIdx.x;
-  if (threadIdx.x < k) dst[threadIdx.x] = dst_row[static_cast<int64_t>(t) * k + threadIdx.x];
+  __syncthreads();
+  if (threadIdx.x < k) {
+    const int p = slot[threadIdx.x];
+    const int i = i0 + threadIdx.x;
+    int d = -1;
+    if (p >= 0) {
+      d = slot_offsets[p] + block_base[static_cast<int64_t>(i / kChunk) * P + p] + cnt[threadIdx.x];
+      src_of[d] = i;
+    }
+    dst[threadIdx.x] = d;
+    dst_row[i] = d;
+  }
   __syncthreads();
   const uint4* src = x + static_cast<int64_t>(t) * row_words;
   for (int c = threadIdx.x; c < row_words; c += kThreads) {
@@ -173,30 +171,19 @@ int launch_dispatch(revive_ctx* ctx, const void* x, const int32_t* topk_phys, in
   const int N = T * c.k;
   const int n_chunks = ceil_div(N, kChunk);
   int32_t* block_hist = reinterpret_cast<int32_t*>(ctx->d_ws + ctx->ws.off_block_hist);
-  int nbits = 1;
-  while ((1 << nbits) < P) ++nbits;
-
-  if (n_chunks > 0) {
-    KernelTimer timer(ctx, REVIVE_K_DISPATCH_COUNT, stream);
-    hipLaunchKernelGGL(dispatch_count_kernel, dim3(n_chunks), dim3(kThreads), 0, stream, topk_phys, N, P, block_hist);
-    REVIVE_HIP(ctx, hipGetLastError());
-  }
+  unsigned int* ticket = reinterpret_cast<unsigned int*>(ctx->d_ws + ctx->ws.off_ticket);
   {
-    KernelTimer timer(ctx, REVIVE_K_DISPATCH_SCAN, stream);
-    hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(kMaxP), 0, stream, block_hist, n_chunks, P, slot_offsets);
+    // with no rows one workgroup still runs, so that slot_offsets becomes all zero
+    KernelTimer timer(ctx, REVIVE_K_DISPATCH_INDEX, stream);
+    hipLaunchKernelGGL(dispatch_index_kernel, dim3(n_chunks > 0 ? n_chunks : 1), dim3(kMaxP), 0, stream, topk_phys, N, P,
+                       block_hist, slot_offsets, ticket);
     REVIVE_HIP(ctx, hipGetLastError());
   }
-  if (n_chunks > 0) {
-    {
-      KernelTimer timer(ctx, REVIVE_K_DISPATCH_PLACE, stream);
-      hipLaunchKernelGGL(dispatch_place_kernel, dim3(n_chunks), dim3(kThreads), 0, stream, topk_phys, N, P, nbits, block_hist,
-                         slot_offsets, dst_row, src_of);
-      REVIVE_HIP(ctx, hipGetLastError());
-    }
+  if (T > 0) {
     KernelTimer timer(ctx, REVIVE_K_DISPATCH_PERMUTE, stream);
     const int row_words = static_cast<int>(c.H * ctx->elem / 16);
-    hipLaunchKernelGGL(dispatch_permute_kernel, dim3(T), dim3(kThreads), 0, stream, static_cast<const uint4*>(x), dst_row, c.k,
-                       row_words, static_cast<uint4*>(x_perm));
+    hipLaunchKernelGGL(dispatch_permute_kernel, dim3(T), dim3(kThreads), 0, stream, static_cast<const uint4*>(x), topk_phys, c.k, P,
+                       block_hist, slot_offsets, row_words, dst_row, src_of, static_cast<uint4*>(x_perm));
     REVIVE_HIP(ctx, hipGetLastError());
   }
   return REVIVE_OK;

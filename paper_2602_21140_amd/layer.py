@@ -70,11 +70,13 @@ class ResidentLayer:
         return self.stats
 
     def forward(self, logits: Optional[torch.Tensor] = None, shared=True, stream=None,
-                overlap_shared=True) -> Dict[str, Optional[torch.Tensor]]:
+                overlap_shared=True, stage_marks: Optional[list] = None) -> Dict[str, Optional[torch.Tensor]]:
         """route -> dispatch -> expert_ffn -> combine into the preallocated buffers (returned).
 
         With overlap_shared the shared expert runs on a side stream next to route/dispatch/routed
-        FFN (fork and join through events, which a stream capture records as graph edges)."""
+        FFN (fork and join through events, which a stream capture records as graph edges).
+        stage_marks, if given, receives five timing events recorded on the main stream: before
+        route, and after route, dispatch, expert_ffn and combine."""
         c, L, b = self.cfg, self.layer, self.buf
         T = c.T
         main = torch.cuda.current_stream() if stream is None else stream
@@ -85,20 +87,31 @@ class ResidentLayer:
             self._side.wait_event(self._ev_fork)
             L.shared_ffn(self.x, self.sh_gate_up, self.sh_down, T, out=b["y_shared"], stream=self._side)
             self._ev_join.record(self._side)
+        def mark():
+            if stage_marks is not None:
+                ev = torch.cuda.Event(enable_timing=True)
+                ev.record(main)
+                stage_marks.append(ev)
+
         out3 = (b["topk_logical"], b["topk_weight"], b["topk_phys"])
+        mark()
         if logits is None:
             L.route(self.x, self.w_router_packed, T, logits=b["logits"], out=out3, stream=main)
         else:
             b["logits"].copy_(logits)
             L.route(None, None, T, logits=b["logits"], logits_given=True, out=out3, stream=main)
+        mark()
         L.dispatch(self.x, b["topk_phys"], T, out=(b["x_perm"], b["slot_offsets"], b["dst_row"], b["src_of"]), stream=main)
+        mark()
         inline_shared = use_shared and not fork
         L.expert_ffn(b["x_perm"], b["slot_offsets"], T, x=self.x, w_sh_gate_up=self.sh_gate_up, w_sh_down=self.sh_down,
                      out=(b["y_perm"], b["y_shared"] if inline_shared else None), shared=inline_shared, stream=main)
         if fork:
             main.wait_event(self._ev_join)
+        mark()
         L.combine(b["y_perm"], b["dst_row"], b["topk_weight"], b["y_shared"] if use_shared else None, T, out=b["out"],
                   stream=main)
+        mark()
         return b
 
     def capture(self, stream: torch.cuda.Stream, overlap_shared=True):
