@@ -121,6 +121,9 @@ def main():
     ap.add_argument("--overlap-shared", action="store_true",
                     help="run the shared expert on a side stream next to route/dispatch (off by default so that "
                          "every kernel of the step runs alone and its timing is its own)")
+    ap.add_argument("--microbatches", type=int, default=0,
+                    help="also time the same batch run as this many microbatches on separate streams inside one graph "
+                         "(a secondary figure under 'microbatch'; the headline value is always the single batch)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of 1 GiB (read 1 GiB, write 1 GiB) so that hardware "
                          "counters collected over this command can be scaled by a kernel of known traffic")
@@ -200,6 +203,27 @@ def main():
         stream.synchronize()
         same_exec = L.graph_exec_id(g.graph) == exec_id
 
+    micro = None
+    if args.microbatches > 1:
+        from paper_2602_21140_amd.layer import MicrobatchPipeline
+        pipe = MicrobatchPipeline(g, args.microbatches)
+        with torch.cuda.stream(stream):
+            pipe.forward(stream)
+            stream.synchronize()
+            pipe.capture(stream)
+            for _ in range(W):
+                pipe.replay(stream)
+            stream.synchronize()
+            m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            m0.record(stream)
+            for _ in range(K):
+                pipe.replay(stream)
+            m1.record(stream)
+            stream.synchronize()
+        micro = {"n": args.microbatches, "ms_per_step": m0.elapsed_time(m1) / K}
+        micro["tokens_per_s"] = cfg.T / (micro["ms_per_step"] * 1e-3)
+        pipe.close()
+
     if args.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)
@@ -255,6 +279,8 @@ def main():
                   "minus_steady_step_ms": first_ms - ms_per_step, "routes_avoid_failed_ranks": all(r[2] for r in remap),
                   "same_graph_exec": same_exec},
     }
+    if micro is not None:
+        result["microbatch"] = micro
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, g, min(args.cpu_sample_tokens, cfg.T))
     g.close()

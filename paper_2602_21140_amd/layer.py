@@ -128,3 +128,85 @@ class ResidentLayer:
 
     def close(self):
         self.layer.close()
+
+
+class MicrobatchPipeline:
+    """The layer over n microbatches of the same batch, each on its own stream (Sec. 2.2: the
+    batch is divided into microbatches so that the stages of different microbatches run
+    concurrently; here the route/dispatch/combine kernels of one microbatch run beside the
+    expert GEMMs of the other).
+
+    Every microbatch has its own context (map tables and workspace are per context) and its own
+    intermediate buffers; weights, inputs and the output tensor are those of `base` (microbatch m
+    reads rows [m*T/n, (m+1)*T/n) of x and writes the same rows of out).  Token t of a microbatch
+    picks replica `t mod count` with t counted inside the microbatch, so topk_phys may differ from
+    the single-batch run where replicas exist; the layer output does not (replicas hold the same
+    weights and every output row is computed by the same arithmetic in the same order)."""
+
+    def __init__(self, base: ResidentLayer, n_micro: int = 2):
+        cfg = base.cfg
+        if n_micro < 1 or cfg.T % n_micro:
+            raise ValueError("T must be a multiple of the number of microbatches")
+        self.base, self.n, self.Tm = base, n_micro, cfg.T // n_micro
+        Tm, k, H, E, P = self.Tm, cfg.k, cfg.H, cfg.E, cfg.P
+        i32, f32 = torch.int32, torch.float32
+        self.parts = []
+        for m in range(n_micro):
+            L = ReviveLayer(cfg, device=base.device, T_max=Tm)
+            L.set_placement(base.p2l)
+            L.update_map(base.failed, expert_failed=base.expert_failed)
+            L.set_expert_weights(base.gu, base.dn)
+            rows = slice(m * Tm, (m + 1) * Tm)
+            buf = dict(
+                x=base.x[rows], out=base.buf["out"][rows],
+                logits=L.empty(Tm, E, dtype=f32), topk_logical=L.empty(Tm, k, dtype=i32),
+                topk_weight=L.empty(Tm, k, dtype=f32), topk_phys=L.empty(Tm, k, dtype=i32),
+                x_perm=L.empty(Tm * k, H), slot_offsets=L.empty(P + 1, dtype=i32), dst_row=L.empty(Tm * k, dtype=i32),
+                src_of=L.empty(Tm * k, dtype=i32), y_perm=L.empty(Tm * k, H),
+                y_shared=L.empty(Tm, H) if base.sh_gate_up is not None else None)
+            self.parts.append((L, buf, torch.cuda.Stream(device=base.device), torch.cuda.Event()))
+        self._fork = torch.cuda.Event()
+        self.graph = None
+
+    def set_failed(self, failed: Iterable[int], stream=None, expert_failed=None) -> Dict[str, int]:
+        """The same map update for every microbatch's context (and the base layer's)."""
+        stats = self.base.set_failed(failed, stream=stream, expert_failed=expert_failed)
+        for L, _buf, _s, _e in self.parts:
+            L.update_map(self.base.failed, stream=stream, expert_failed=expert_failed)
+        return stats
+
+    def forward(self, stream: Optional[torch.cuda.Stream] = None):
+        """Fork from `stream`, run every microbatch's four calls on its own stream, join."""
+        base, Tm = self.base, self.Tm
+        main = torch.cuda.current_stream() if stream is None else stream
+        self._fork.record(main)
+        for L, b, s, done in self.parts:
+            s.wait_event(self._fork)
+            L.route(b["x"], base.w_router_packed, Tm, logits=b["logits"],
+                    out=(b["topk_logical"], b["topk_weight"], b["topk_phys"]), stream=s)
+            L.dispatch(b["x"], b["topk_phys"], Tm, out=(b["x_perm"], b["slot_offsets"], b["dst_row"], b["src_of"]), stream=s)
+            shared = base.sh_gate_up is not None
+            L.expert_ffn(b["x_perm"], b["slot_offsets"], Tm, x=b["x"], w_sh_gate_up=base.sh_gate_up, w_sh_down=base.sh_down,
+                         out=(b["y_perm"], b["y_shared"]), shared=shared, stream=s)
+            L.combine(b["y_perm"], b["dst_row"], b["topk_weight"], b["y_shared"], Tm, out=b["out"], stream=s)
+            done.record(s)
+        for _L, _b, _s, done in self.parts:
+            main.wait_event(done)
+        return base.buf["out"]
+
+    def capture(self, stream: torch.cuda.Stream):
+        """Record one forward (all microbatches, fork and join included) into one graph."""
+        L0 = self.parts[0][0]
+        L0.graph_begin(stream)
+        try:
+            self.forward(stream)
+        finally:
+            self.graph = L0.graph_end(stream)
+        return self.graph
+
+    def replay(self, stream: torch.cuda.Stream):
+        self.parts[0][0].graph_launch(self.graph, stream)
+
+    def close(self):
+        for L, _b, _s, _e in self.parts:
+            L.close()
