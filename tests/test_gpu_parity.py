@@ -37,6 +37,10 @@ SMALL = {
                   n_unprotected=-1),
     "k128": _small("c2", T=600, H=128, I=64, I_shared=128, E=16, k=3, n_ranks=4, slots_per_rank=5, failed_ranks=(),
                    n_unprotected=-1),
+    # the largest expert count, slot count, top-k and group count the library accepts; ranks 3 and 4 are neighbours,
+    # so rank 4's primaries lose both copies (8 lost experts), rank 40 only degrades
+    "max": _small("c3", T=300, H=128, I=64, I_shared=64, E=512, k=32, n_ranks=64, slots_per_rank=16, max_replicas=2,
+                  n_group=32, topk_group=8, failed_ranks=(3, 4, 40), n_unprotected=-1),
 }
 
 
