@@ -6,12 +6,13 @@
 // rank's slots never appear in topk_phys (Sec. 3.4), so its segment is empty (Sec. 3.5).
 //
 // Two kernels, both with grids fixed by T:
-//   index    per-chunk LDS histogram of the slot ids -> block_hist[chunk][P]; the workgroup that
-//            finishes last turns the columns into running sums over the chunks and scans the
-//            totals over P -> block_hist (bases), slot_offsets
-//   permute  one workgroup per token: stable destination of each of its k routed rows (rows of
-//            the same chunk and slot that come before it are counted from topk_phys, which is
-//            L2-resident), then the row is read once and written to its k destinations
+//   index    per chunk of 1024 routed rows: stable rank of every row among the rows of its slot
+//            in the chunk (-> dst_row, for now) and the chunk's histogram -> block_hist[chunk][P];
+//            the workgroup that finishes last turns the columns into running sums over the
+//            chunks and scans the totals over P -> block_hist (bases), slot_offsets
+//   permute  one workgroup per token: destination of each of its k routed rows = slot offset +
+//            chunk base + rank in the chunk (-> dst_row, src_of), then the row is read once and
+//            written to its k destinations
 #include "ctx.hpp"
 
 namespace revive {
@@ -20,28 +21,54 @@ namespace {
 
 constexpr int kChunk = kDispatchChunk;  // routed rows per workgroup of the index kernel
 constexpr int kThreads = 256;
-static_assert(kMaxK < kChunk, "a token's rows touch at most two chunks");
 
 // One workgroup of kMaxP threads per chunk: a thread handles one routed row of the histogram and,
 // in the workgroup that finishes last, one slot column of the scan.
 // `ticket` counts finished workgroups; the last one resets it, so it is zero between launches.
-__global__ __launch_bounds__(kMaxP) void dispatch_index_kernel(const int32_t* __restrict__ topk_phys, int N, int P,
+__global__ __launch_bounds__(kMaxP) void dispatch_index_kernel(const int32_t* __restrict__ topk_phys, int N, int P, int nbits,
                                                                int32_t* block_hist, int32_t* __restrict__ slot_offsets,
-                                                               unsigned int* ticket) {
+                                                               int32_t* __restrict__ rank_in_chunk, unsigned int* ticket) {
   static_assert(kChunk == kMaxP, "one routed row and one slot column per thread");
-  __shared__ int hist[kMaxP];
-  __shared__ int wave_sums[kMaxP / 64];
+  constexpr int kWaves = kMaxP / 64;
+  __shared__ uint8_t wave_cnt[kWaves][kMaxP];  // rows of a slot held by each 64-row wavefront of the chunk (<= 64)
+  __shared__ int wave_sums[kWaves];
   __shared__ int last_flag;
   const int p = threadIdx.x;
-  hist[p] = 0;
+  const int lane = p & 63, wave = p >> 6;
+  for (int j = p; j < kWaves * P; j += kMaxP) wave_cnt[j / P][j % P] = 0;
   __syncthreads();
+  // Rows are taken in ascending index: wavefront w holds rows [64w, 64w + 64) of the chunk.  The
+  // lanes that hold the same slot are found with one ballot per bit of the slot id.
   const int i = blockIdx.x * kChunk + threadIdx.x;
+  int q = -1;
   if (i < N) {
-    const int q = topk_phys[i];
-    if (q >= 0 && q < P) atomicAdd(&hist[q], 1);
+    q = topk_phys[i];
+    if (q < 0 || q >= P) q = -1;  // slot id outside [0, P): the row is dropped
   }
+  const bool valid = q >= 0;
+  unsigned long long peers = __ballot(valid);
+  for (int b = 0; b < nbits; ++b) {
+    const bool bit = (q >> b) & 1;
+    const unsigned long long m = __ballot(valid && bit);
+    peers &= bit ? m : ~m;
+  }
+  const unsigned long long below = peers & ((1ull << lane) - 1ull);
+  if (valid && below == 0) wave_cnt[wave][q] = static_cast<uint8_t>(__popcll(peers));
   __syncthreads();
-  if (p < P) block_hist[static_cast<int64_t>(blockIdx.x) * P + p] = hist[p];
+  if (i < N) {
+    int r = -1;
+    if (valid) {
+      r = __popcll(below);
+      for (int w = 0; w < wave; ++w) r += wave_cnt[w][q];
+    }
+    rank_in_chunk[i] = r;
+  }
+  if (p < P) {
+    int total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) total += wave_cnt[w][p];
+    block_hist[static_cast<int64_t>(blockIdx.x) * P + p] = total;
+  }
 
   // Publish this chunk's histogram device-wide, then take a ticket; only the workgroup holding the
   // last ticket goes on (nobody waits for anybody).  The barrier orders the workgroup's stores
@@ -79,7 +106,6 @@ __global__ __launch_bounds__(kMaxP) void dispatch_index_kernel(const int32_t* __
     }
   }
   // exclusive scan of `run` over the slots: wavefront scan, then scan of the wavefront totals
-  const int lane = p & 63, wave = p >> 6;
   int incl = run;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
@@ -89,14 +115,14 @@ __global__ __launch_bounds__(kMaxP) void dispatch_index_kernel(const int32_t* __
   if (lane == 63) wave_sums[wave] = incl;
   __syncthreads();
   if (wave == 0) {
-    const int w = lane < kMaxP / 64 ? wave_sums[lane] : 0;
+    const int w = lane < kWaves ? wave_sums[lane] : 0;
     int wi = w;
 #pragma unroll
-    for (int o = 1; o < kMaxP / 64; o <<= 1) {
+    for (int o = 1; o < kWaves; o <<= 1) {
       const int u = __shfl_up(wi, o);
       if (lane >= o) wi += u;
     }
-    if (lane < kMaxP / 64) wave_sums[lane] = wi - w;
+    if (lane < kWaves) wave_sums[lane] = wi - w;
   }
   __syncthreads();
   const int excl = wave_sums[wave] + incl - run;
@@ -108,48 +134,26 @@ __global__ __launch_bounds__(kMaxP) void dispatch_index_kernel(const int32_t* __
 }
 
 // One workgroup per token; 16-byte words.  Routed row i = t*k + j goes to
-//   slot_offsets[p] + (rows of slot p in earlier chunks) + (rows of slot p earlier in i's chunk),
-// the position a stable counting sort by slot gives it.
+//   slot_offsets[p] + (rows of slot p in earlier chunks) + (rank of i among the rows of slot p in its chunk),
+// the position a stable counting sort by slot gives it.  dst_row arrives holding the rank (or -1).
 __global__ __launch_bounds__(kThreads) void dispatch_permute_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ topk_phys,
                                                                     int k, int P, const int32_t* __restrict__ block_base,
                                                                     const int32_t* __restrict__ slot_offsets, int row_words,
                                                                     int32_t* __restrict__ dst_row, int32_t* __restrict__ src_of,
                                                                     uint4* __restrict__ x_perm) {
-  __shared__ int slot[kMaxK], cnt[kMaxK], dst[kMaxK];
+  __shared__ int dst[kMaxK];
   const int t = blockIdx.x;
-  const int i0 = t * k;
   if (threadIdx.x < k) {
-    int p = topk_phys[i0 + threadIdx.x];
-    if (p < 0 || p >= P) p = -1;  // slot id outside [0, P): the row is dropped
-    slot[threadIdx.x] = p;
-    cnt[threadIdx.x] = 0;
-  }
-  __syncthreads();
-  const int lane = threadIdx.x & 63;
-  const int first = (i0 / kChunk) * kChunk;  // start of the chunk that holds row i0
-  const int last_row = i0 + k - 1;
-  for (int b = first; b < last_row; b += kThreads) {
-    const int idx = b + threadIdx.x;
-    const int v = idx < last_row ? topk_phys[idx] : -1;
-    for (int j = 0; j < k; ++j) {
-      const int ij = i0 + j;
-      const int start_j = (ij / kChunk) * kChunk;
-      const bool hit = v >= 0 && v == slot[j] && idx >= start_j && idx < ij;
-      const unsigned long long m = __ballot(hit);
-      if (lane == 0 && m) atomicAdd(&cnt[j], __popcll(m));
-    }
-  }
-  __syncthreads();
-  if (threadIdx.x < k) {
-    const int p = slot[threadIdx.x];
-    const int i = i0 + threadIdx.x;
+    const int i = t * k + threadIdx.x;
+    const int r = dst_row[i];
     int d = -1;
-    if (p >= 0) {
-      d = slot_offsets[p] + block_base[static_cast<int64_t>(i / kChunk) * P + p] + cnt[threadIdx.x];
+    if (r >= 0) {
+      const int p = topk_phys[i];
+      d = slot_offsets[p] + block_base[static_cast<int64_t>(i / kChunk) * P + p] + r;
       src_of[d] = i;
+      dst_row[i] = d;
     }
     dst[threadIdx.x] = d;
-    dst_row[i] = d;
   }
   __syncthreads();
   const uint4* src = x + static_cast<int64_t>(t) * row_words;
@@ -172,11 +176,13 @@ int launch_dispatch(revive_ctx* ctx, const void* x, const int32_t* topk_phys, in
   const int n_chunks = ceil_div(N, kChunk);
   int32_t* block_hist = reinterpret_cast<int32_t*>(ctx->d_ws + ctx->ws.off_block_hist);
   unsigned int* ticket = reinterpret_cast<unsigned int*>(ctx->d_ws + ctx->ws.off_ticket);
+  int nbits = 1;
+  while ((1 << nbits) < P) ++nbits;
   {
     // with no rows one workgroup still runs, so that slot_offsets becomes all zero
     KernelTimer timer(ctx, REVIVE_K_DISPATCH_INDEX, stream);
-    hipLaunchKernelGGL(dispatch_index_kernel, dim3(n_chunks > 0 ? n_chunks : 1), dim3(kMaxP), 0, stream, topk_phys, N, P,
-                       block_hist, slot_offsets, ticket);
+    hipLaunchKernelGGL(dispatch_index_kernel, dim3(n_chunks > 0 ? n_chunks : 1), dim3(kMaxP), 0, stream, topk_phys, N, P, nbits,
+                       block_hist, slot_offsets, dst_row, ticket);
     REVIVE_HIP(ctx, hipGetLastError());
   }
   if (T > 0) {
