@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256) void route_topk_kernel(RouteParams p) {
 }
 
 // Router logits for a small router (E <= 128) without LDS staging.  A workgroup of KS wavefronts
-// owns 32 tokens and all E experts; wavefront w multiplies the w-th slice of the hidden dimension
+// owns 32 tokens and NTN tiles of 32 experts (blockIdx.y selects which); wavefront w multiplies the w-th slice of the hidden dimension
 // with operands loaded straight from global memory in MFMA fragment order, and the KS partial
 // sums are added in wavefront order through LDS (a fixed order: the result is deterministic).
 // Per 64-wide K block a lane reads 64 contiguous bytes of its token row (lanes l and l+32 cover
@@ -160,13 +160,14 @@ __global__ __launch_bounds__(64 * KS) void router_direct_kernel(const uint16_t* 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 31, half = lane >> 5;
   const int row0 = blockIdx.x * 32;
+  const int e0 = blockIdx.y * (NTN * 32);  // first expert of this workgroup
   const int kq = H / KS;  // K range of one wavefront, a multiple of 64
   const int64_t koff = static_cast<int64_t>(wave) * kq + half * 32;
   const unsigned char* a_ptr = reinterpret_cast<const unsigned char*>(x + static_cast<int64_t>(min(row0 + r, T - 1)) * H + koff);
   const unsigned char* b_ptr[NTN];
 #pragma unroll
   for (int tn = 0; tn < NTN; ++tn)
-    b_ptr[tn] = reinterpret_cast<const unsigned char*>(w + static_cast<int64_t>(min(tn * 32 + r, E - 1)) * H + koff);
+    b_ptr[tn] = reinterpret_cast<const unsigned char*>(w + static_cast<int64_t>(min(e0 + tn * 32 + r, E - 1)) * H + koff);
 
   f32x16 acc[NTN];
 #pragma unroll
@@ -232,7 +233,7 @@ __global__ __launch_bounds__(64 * KS) void router_direct_kernel(const uint16_t* 
       if (row < T) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int col = tn * 32 + q * 8 + half * 4;
+          const int col = e0 + tn * 32 + q * 8 + half * 4;
 #pragma unroll
           for (int rr = 0; rr < 4; ++rr)
             if (col + rr < E) logits[static_cast<int64_t>(row) * E + col + rr] = acc[tn][q * 4 + rr];
@@ -252,7 +253,7 @@ int launch_router_direct(revive_ctx* ctx, const void* x, const void* w, float* l
                                         static_cast<int>(lds)));
     configured = true;
   }
-  hipLaunchKernelGGL(kern, dim3(ceil_div(T, 32)), dim3(64 * KS), lds, stream, static_cast<const uint16_t*>(x),
+  hipLaunchKernelGGL(kern, dim3(ceil_div(T, 32), ceil_div(ctx->cfg.E, NTN * 32)), dim3(64 * KS), lds, stream, static_cast<const uint16_t*>(x),
                      static_cast<const uint16_t*>(w), logits, T, ctx->cfg.E, ctx->cfg.H);
   return check_hip(ctx, hipGetLastError(), "router_direct launch");
 }
@@ -264,9 +265,12 @@ int launch_router_gemm(revive_ctx* ctx, const void* x, const void* w, float* log
   KernelTimer timer(ctx, REVIVE_K_ROUTER_GEMM, stream);
   if (c.dtype == REVIVE_DTYPE_BF16 && c.E <= 128 && c.H % 256 == 0 &&
       static_cast<int64_t>(ceil_div(T, 32)) * c.E * c.H * 2 <= (128ll << 20)) {
-    // small router: every 32-token workgroup re-reads the whole router matrix from L2
+    // small router: every 32-token workgroup re-reads its part of the router matrix from L2.  With few
+    // token blocks every 32-expert tile gets a workgroup of its own (more workgroups, and less
+    // to pull through one CU's L1), otherwise one workgroup serves all experts of its tokens.
     const bool ks8 = c.H % 512 == 0;
-    switch (ceil_div(c.E, 32)) {
+    const bool split_experts = ceil_div(T, 32) < 512;
+    switch (split_experts ? 1 : ceil_div(c.E, 32)) {
       case 1: return ks8 ? launch_router_direct<1, 8>(ctx, x, w, logits, T, stream) : launch_router_direct<1, 4>(ctx, x, w, logits, T, stream);
       case 2: return ks8 ? launch_router_direct<2, 8>(ctx, x, w, logits, T, stream) : launch_router_direct<2, 4>(ctx, x, w, logits, T, stream);
       case 3: return launch_router_direct<3, 4>(ctx, x, w, logits, T, stream);
