@@ -32,23 +32,35 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
   __syncthreads();
   for (int c = threadIdx.x; c < row_words; c += 256) {
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int j = 0; j < k; ++j) {
-      const int r = rows[j];
-      if (r < 0) continue;
-      const float w = wts[j];
-      const uint4 v = y_perm[static_cast<int64_t>(r) * row_words + c];
-      if (BF16) {
-        acc[0] = fmaf(w, bf16_lo(v.x), acc[0]); acc[1] = fmaf(w, bf16_hi(v.x), acc[1]);
-        acc[2] = fmaf(w, bf16_lo(v.y), acc[2]); acc[3] = fmaf(w, bf16_hi(v.y), acc[3]);
-        acc[4] = fmaf(w, bf16_lo(v.z), acc[4]); acc[5] = fmaf(w, bf16_hi(v.z), acc[5]);
-        acc[6] = fmaf(w, bf16_lo(v.w), acc[6]); acc[7] = fmaf(w, bf16_hi(v.w), acc[7]);
-      } else {
-        acc[0] = fmaf(w, __uint_as_float(v.x), acc[0]); acc[1] = fmaf(w, __uint_as_float(v.y), acc[1]);
-        acc[2] = fmaf(w, __uint_as_float(v.z), acc[2]); acc[3] = fmaf(w, __uint_as_float(v.w), acc[3]);
+    uint4 sh = make_uint4(0, 0, 0, 0);
+    if (y_shared) sh = y_shared[static_cast<int64_t>(t) * row_words + c];
+    // the gathers of up to eight routed rows are issued together, then added in ascending j
+    for (int j0 = 0; j0 < k; j0 += 8) {
+      uint4 v[8];
+      bool on[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int r = j0 + u < k ? rows[j0 + u] : -1;
+        on[u] = r >= 0;
+        v[u] = on[u] ? y_perm[static_cast<int64_t>(r) * row_words + c] : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (!on[u]) continue;
+        const float w = wts[j0 + u];
+        if (BF16) {
+          acc[0] = fmaf(w, bf16_lo(v[u].x), acc[0]); acc[1] = fmaf(w, bf16_hi(v[u].x), acc[1]);
+          acc[2] = fmaf(w, bf16_lo(v[u].y), acc[2]); acc[3] = fmaf(w, bf16_hi(v[u].y), acc[3]);
+          acc[4] = fmaf(w, bf16_lo(v[u].z), acc[4]); acc[5] = fmaf(w, bf16_hi(v[u].z), acc[5]);
+          acc[6] = fmaf(w, bf16_lo(v[u].w), acc[6]); acc[7] = fmaf(w, bf16_hi(v[u].w), acc[7]);
+        } else {
+          acc[0] = fmaf(w, __uint_as_float(v[u].x), acc[0]); acc[1] = fmaf(w, __uint_as_float(v[u].y), acc[1]);
+          acc[2] = fmaf(w, __uint_as_float(v[u].z), acc[2]); acc[3] = fmaf(w, __uint_as_float(v[u].w), acc[3]);
+        }
       }
     }
     if (y_shared) {
-      const uint4 v = y_shared[static_cast<int64_t>(t) * row_words + c];
+      const uint4 v = sh;
       if (BF16) {
         acc[0] += bf16_lo(v.x); acc[1] += bf16_hi(v.x); acc[2] += bf16_lo(v.y); acc[3] += bf16_hi(v.y);
         acc[4] += bf16_lo(v.z); acc[5] += bf16_hi(v.z); acc[6] += bf16_lo(v.w); acc[7] += bf16_hi(v.w);
