@@ -25,9 +25,8 @@ constexpr int kTileM_bf16 = 256;
 constexpr int kTileM_f32 = 64;
 
 // One row-tile of a grouped GEMM.  All row-tiles of a group (physical slot) carry the same
-// record except for their position: tile j covers rows [group_begin + j*tile_m,
-// min(group_end, group_begin + (j+1)*tile_m)).  The group's weight matrices ride along so that a
-// workgroup needs one read to know everything about its tile.
+// record except for their position; tile_span() gives the rows of tile j.  The group's weight
+// matrices ride along so that a workgroup needs one read to know everything about its tile.
 struct MTile {
   int32_t group;
   int32_t group_begin;
@@ -35,6 +34,27 @@ struct MTile {
   int32_t pad;          // (row-tiles of the group << 16) | position of this tile inside its group
   const void* w[2];     // the group's gate/up and down matrices (null when the caller uses a table)
 };
+
+// Rows [row_begin, row_end) of tile j of a group with rows [begin, end) cut into G = ceil(rows / tile_m)
+// tiles.  Tiles are tile_m rows high except the last two, which share their rows about evenly (the
+// first of them rounded up to 64 rows): a slot that overflows a tile by a few rows would otherwise
+// get a second tile that streams the whole weight matrix for almost no work, ahead of and out of
+// step with its neighbour, so that the weights come from HBM twice.  The split costs no extra
+// MFMA time: the 32-row sub-tiles are dealt to two wavefront rows, and ceil(a/2) + ceil(b/2) over
+// the two tiles is the same for both ways of cutting.
+__host__ __device__ inline void tile_span(int begin, int end, int G, int j, int tile_m, int& row_begin, int& row_end) {
+  if (G >= 2 && j >= G - 2) {
+    const int base = begin + (G - 2) * tile_m;
+    const int both = end - base;  // tile_m + rows of the last tile
+    int a = ((both + 1) / 2 + 63) & ~63;
+    if (a > tile_m) a = tile_m;
+    row_begin = j == G - 2 ? base : base + a;
+    row_end = j == G - 2 ? base + a : end;
+  } else {
+    row_begin = begin + j * tile_m;
+    row_end = row_begin + tile_m < end ? row_begin + tile_m : end;
+  }
+}
 
 // Device-resident map, one contiguous blob at a fixed address so that one copy updates it.
 struct MapLayout {

@@ -121,8 +121,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
   if (g.tiles) {
     const MTile t = g.tiles[m_idx];
     group = t.group;
-    row_begin = t.group_begin + (t.pad & 0xFFFF) * BM;
-    row_end = min(t.group_end, row_begin + BM);
+    tile_span(t.group_begin, t.group_end, t.pad >> 16, t.pad & 0xFFFF, BM, row_begin, row_end);
   } else {
     row_begin = m_idx * BM;
     row_end = min(g.M, row_begin + BM);
@@ -371,8 +370,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
       n_idx = r / in_group;
       j = r - n_idx * in_group;
     }
-    row_begin = t.group_begin + j * BM;
-    row_end = min(t.group_end, row_begin + BM);
+    tile_span(t.group_begin, t.group_end, in_group, j, BM, row_begin, row_end);
     Bbase = static_cast<const unsigned char*>(g.b_sel >= 0 ? t.w[g.b_sel] : (g.B_tab ? g.B_tab[t.group] : g.B_one));
   } else {
     row_begin = m_idx * BM;

@@ -42,8 +42,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32Args g) {
   if (g.tiles) {
     const MTile t = g.tiles[m_idx];
     group = t.group;
-    row_begin = t.group_begin + (t.pad & 0xFFFF) * BM;
-    row_end = min(t.group_end, row_begin + BM);
+    tile_span(t.group_begin, t.group_end, t.pad >> 16, t.pad & 0xFFFF, BM, row_begin, row_end);
   } else {
     row_begin = m_idx * BM;
     row_end = min(g.M, row_begin + BM);
