@@ -89,7 +89,10 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
 // touches (same logical chunk) fall on 16 distinct 16-byte bank groups.
 __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
-__device__ __forceinline__ float silu_f32(float z) { return z / (1.0f + __expf(-z)); }
+// silu(z) = z / (1 + exp(-z)) with the hardware reciprocal (1 ulp) instead of an IEEE division: the
+// result is rounded to bf16 right after, and the division sequence is ten instructions per output.
+// exp overflows to +inf for z < -88, where the product is the correct -0.
+__device__ __forceinline__ float silu_f32(float z) { return z * __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
 
 // KID (the library's kernel id) only gives each use of the kernel its own symbol name in profiles.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int KID>
