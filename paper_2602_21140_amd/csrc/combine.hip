@@ -11,10 +11,12 @@ namespace {
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
-__device__ __forceinline__ uint32_t to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return u >> 16;
+// Two fp32 -> one word of two bf16 (round-to-nearest-even), one v_cvt_pk_bf16_f32.
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 // One workgroup per token, 16-byte words (8 bf16 or 4 fp32 per thread and step).
@@ -71,10 +73,10 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
     }
     uint4 o;
     if (BF16) {
-      o.x = to_bf16(acc[0]) | (to_bf16(acc[1]) << 16);
-      o.y = to_bf16(acc[2]) | (to_bf16(acc[3]) << 16);
-      o.z = to_bf16(acc[4]) | (to_bf16(acc[5]) << 16);
-      o.w = to_bf16(acc[6]) | (to_bf16(acc[7]) << 16);
+      o.x = pack_bf16(acc[0], acc[1]);
+      o.y = pack_bf16(acc[2], acc[3]);
+      o.z = pack_bf16(acc[4], acc[5]);
+      o.w = pack_bf16(acc[6], acc[7]);
     } else {
       o.x = __float_as_uint(acc[0]); o.y = __float_as_uint(acc[1]);
       o.z = __float_as_uint(acc[2]); o.w = __float_as_uint(acc[3]);

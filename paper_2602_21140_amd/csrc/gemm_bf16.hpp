@@ -83,6 +83,14 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
   return u >> 16;
 }
 
+// Two fp32 -> one word of two bf16 (round-to-nearest-even), one v_cvt_pk_bf16_f32.
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
 // LDS swizzle.  The gfx950 LDS has 64 four-byte banks (256 B per clock) and serves a 16-byte
 // per-lane access in groups of 16 lanes.  Tile rows are 128 bytes, so rows r and r+2 start on the
 // same bank; XOR-ing the 16-byte chunk index with (row >> 1) & 7 makes the 16 rows a lane group
@@ -623,8 +631,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
           if (EPI == EPI_SWIGLU) v[r] = silu_f32(acc[tm][tn][q * 4 + r]) * acc[tm][tn + TN / 2][q * 4 + r];
           else v[r] = acc[tm][tn][q * 4 + r];
         }
-        u32x2 o = {f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16),
-                   f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16)};
+        u32x2 o = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
         *reinterpret_cast<u32x2*>(slice + (tm * 32 + (lane & 31)) * ROWB + (tn * 32 + q * 8 + (lane >> 5) * 4) * 2) = o;
       }
     }
