@@ -132,6 +132,16 @@ static int check_config(const revive_config& c) {
   if (c.H % 8 != 0) return fail(nullptr, REVIVE_EINVAL, "config: H must be a multiple of 8");
   if (c.dtype == REVIVE_DTYPE_BF16 && (c.H % 64 != 0 || c.I % 64 != 0 || c.I_shared % 64 != 0))
     return fail(nullptr, REVIVE_EINVAL, "config: bf16 needs H, I and I_shared multiples of 64");
+  if (c.dtype == REVIVE_DTYPE_BF16) {
+    // the GEMM addresses a weight matrix and one row-tile of activations with 32-bit byte offsets
+    const int64_t widest = std::max<int64_t>(c.I, c.I_shared);
+    const int64_t pad = 128;
+    const int64_t gate_up_bytes = 2 * ((widest + pad - 1) / pad * pad) * c.H * 2;
+    const int64_t down_bytes = ((static_cast<int64_t>(c.H) + pad - 1) / pad * pad) * widest * 2;
+    const int64_t tile_bytes = 256 * std::max<int64_t>(c.H, widest) * 2;
+    if (gate_up_bytes >= (1ll << 31) || down_bytes >= (1ll << 31) || tile_bytes >= (1ll << 31))
+      return fail(nullptr, REVIVE_EINVAL, "config: H * I too large for one expert matrix (2 GiB limit)");
+  }
   if (c.dtype == REVIVE_DTYPE_F32 && (c.I % 4 != 0 || c.I_shared % 4 != 0))
     return fail(nullptr, REVIVE_EINVAL, "config: fp32 needs I and I_shared multiples of 4");
   if (static_cast<int64_t>(c.T_max) * c.k >= (1ll << 30)) return fail(nullptr, REVIVE_EINVAL, "config: T_max * k too large");

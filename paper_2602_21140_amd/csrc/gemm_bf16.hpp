@@ -398,7 +398,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
 
   // ---- copy plan: instruction i of this wavefront fills rows [(wave*CP_x + i)*16, +16) of the A
   // (then B) part of a stage; lane l owns row l/4 of those, physical chunk l%4.
-  const unsigned char* cp_src[CP];
+  // The source address of a copy is a wavefront-uniform 64-bit base (the tile's first row of A, the
+  // weight matrix) kept in scalar registers plus a 32-bit per-lane byte offset that never changes:
+  // walking K only advances the two scalar bases, no vector arithmetic.
+  uint32_t cp_off[CP];
   int cp_dst[CP];  // wavefront-uniform LDS offset of the 1 KiB window inside a stage
 #pragma unroll
   for (int i = 0; i < CP; ++i) {
@@ -407,8 +410,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
     const int row = blk * 16 + (lane >> 2);
     const int chunk = (lane & 3) ^ swz32(row);
     if (isA) {
-      const int grow = min(row_begin + row, row_end - 1);
-      cp_src[i] = Abase + (static_cast<int64_t>(grow) * g.lda + chunk * 8) * 2;
+      const int rrow = min(row, row_end - row_begin - 1);  // rows past the tile re-read its last row
+      cp_off[i] = static_cast<uint32_t>((static_cast<int64_t>(rrow) * g.lda + chunk * 8) * 2);
       cp_dst[i] = blk * 1024;
     } else {
       if (g.b_tiled) {
@@ -421,7 +424,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
           R = min(n0 + row, g.b_rows_pad - 1);
         }
         const int64_t panel = static_cast<int64_t>(R / kWeightTileRows) * (g.K / kWeightTileK) * kWeightTileRows;
-        cp_src[i] = Bbase + ((panel + (R % kWeightTileRows)) * kWeightTileK + chunk * 8) * 2;
+        cp_off[i] = static_cast<uint32_t>(((panel + (R % kWeightTileRows)) * kWeightTileK + chunk * 8) * 2);
       } else {
         int brow;
         if (EPI == EPI_SWIGLU) {
@@ -431,7 +434,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
         } else {
           brow = min(n0 + row, g.n_out - 1);
         }
-        cp_src[i] = Bbase + (static_cast<int64_t>(brow) * g.ldb + chunk * 8) * 2;
+        cp_off[i] = static_cast<uint32_t>((static_cast<int64_t>(brow) * g.ldb + chunk * 8) * 2);
       }
       cp_dst[i] = BM * 64 + blk * 1024;
     }
@@ -441,15 +444,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   // every LDS wait into a full drain, which would undo the software pipeline.  Issued this way the
   // copies are invisible to that bookkeeping and are waited for explicitly before each barrier.
   const uint32_t smem_lds = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lptr)smem));
+  auto uniform64 = [](uint64_t v) {
+    // the builtin returns a signed int: widen both halves as unsigned
+    const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(v >> 32)));
+    const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(v)));
+    return (static_cast<uint64_t>(hi) << 32) | lo;
+  };
+  const uint64_t base_a = uniform64(reinterpret_cast<uint64_t>(Abase) + static_cast<uint64_t>(row_begin) * g.lda * 2);
+  const uint64_t base_b = uniform64(reinterpret_cast<uint64_t>(Bbase));
+  const uint32_t kstep_b = g.b_tiled ? kWeightTileRows * kWeightTileK * 2 : 64;  // bytes between K-steps of B
   auto issue_copy = [&](int kt) {
     const uint32_t stage = smem_lds + stage_of(kt) * STAGE;
-    const int64_t koff_a = static_cast<int64_t>(kt) * 64;  // 32 bf16 further along the row
-    const int64_t koff_b = g.b_tiled ? static_cast<int64_t>(kt) * (kWeightTileRows * kWeightTileK * 2) : koff_a;
+    const uint64_t src_a = base_a + static_cast<uint64_t>(kt) * 64;  // 32 bf16 further along the row
+    const uint64_t src_b = base_b + static_cast<uint64_t>(kt) * kstep_b;
 #pragma unroll
     for (int i = 0; i < CP; ++i) {
-      const unsigned char* src = cp_src[i] + (i < CP_A ? koff_a : koff_b);
       const uint32_t dst = __builtin_amdgcn_readfirstlane(stage + cp_dst[i]);
-      asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(dst) : "memory", "m0");
+      asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(cp_off[i]), "s"(i < CP_A ? src_a : src_b), "s"(dst) : "memory", "m0");
     }
   };
 
