@@ -76,13 +76,14 @@ struct Bf16Ffn {  // one SwiGLU FFN: rows of A -> h -> y
   int I;
   const MTile* tiles; const int32_t* tile_count; int M;
   int max_m_tiles;
+  int h_rows;  // rows of the intermediate h, which is kept K-panel-major: [I/32][h_rows][32]
 };
 
 GemmArgs gate_up_args(const revive_ctx* ctx, const Bf16Ffn& f, int bn_out) {
   GemmArgs a{};
   a.A = f.A; a.lda = ctx->cfg.H;
   a.B_tab = f.gu_tab; a.B_one = f.gu_one; a.ldb = ctx->cfg.H;
-  a.C = f.h; a.ldc = f.I;
+  a.C = f.h; a.ldc = f.I; a.c_rows = f.h_rows;
   a.n_out = f.I; a.K = ctx->cfg.H;
   a.tiles = f.tiles; a.tile_count = f.tile_count; a.M = f.M;
   a.n_col_tiles = ceil_div(f.I, bn_out);
@@ -94,7 +95,7 @@ GemmArgs gate_up_args(const revive_ctx* ctx, const Bf16Ffn& f, int bn_out) {
 
 GemmArgs down_args(const revive_ctx* ctx, const Bf16Ffn& f, int bn_out) {
   GemmArgs d{};
-  d.A = f.h; d.lda = f.I;
+  d.A = f.h; d.lda = f.I; d.a_rows = f.h_rows;
   d.B_tab = f.dn_tab; d.B_one = f.dn_one; d.ldb = f.I;
   d.C = f.y; d.ldc = ctx->cfg.H;
   d.n_out = ctx->cfg.H; d.K = f.I;
@@ -188,11 +189,11 @@ int launch_expert_ffn(revive_ctx* ctx, const void* x_perm, const int32_t* slot_o
   const int bound = max_tiles(N, ctx->P, tile_m);
   constexpr int GU = REVIVE_K_FFN_GATE_UP, DN = REVIVE_K_FFN_DOWN;
   if (bf16) {
-    Bf16Ffn routed{x_perm, w_gate_up, nullptr, w_down, nullptr, h, y_perm, c.I, tiles, tile_count, 0, bound};
+    Bf16Ffn routed{x_perm, w_gate_up, nullptr, w_down, nullptr, h, y_perm, c.I, tiles, tile_count, 0, bound, static_cast<int>(N)};
     if (!y_shared) return bf16_ffn<GU, DN>(ctx, routed, nullptr, stream);
     // routed and shared experts in the same two launches
     Bf16Ffn shared{x, nullptr, w_sh_gate_up, nullptr, w_sh_down, ctx->d_ws + ctx->ws.off_h_shared, y_shared, c.I_shared,
-                   nullptr, nullptr, T, ceil_div(T, tile_m)};
+                   nullptr, nullptr, T, ceil_div(T, tile_m), T};
     return bf16_ffn<GU, DN>(ctx, routed, &shared, stream);
   }
   int rc = f32_gemm_pair<GU, DN>(ctx, x_perm, w_gate_up, nullptr, w_down, nullptr, h, y_perm, c.I, tiles, tile_count, 0, bound, stream);
@@ -208,7 +209,7 @@ int launch_shared_ffn(revive_ctx* ctx, const void* x, const void* w_sh_gate_up, 
   void* h_shared = ctx->d_ws + ctx->ws.off_h_shared;
   constexpr int SGU = REVIVE_K_FFN_SHARED_GATE_UP, SDN = REVIVE_K_FFN_SHARED_DOWN;
   if (bf16) {
-    Bf16Ffn shared{x, nullptr, w_sh_gate_up, nullptr, w_sh_down, h_shared, y_shared, c.I_shared, nullptr, nullptr, T, dense_tiles};
+    Bf16Ffn shared{x, nullptr, w_sh_gate_up, nullptr, w_sh_down, h_shared, y_shared, c.I_shared, nullptr, nullptr, T, dense_tiles, T};
     return bf16_ffn<SGU, SDN>(ctx, shared, nullptr, stream);
   }
   return f32_gemm_pair<SGU, SDN>(ctx, x, nullptr, w_sh_gate_up, nullptr, w_sh_down, h_shared, y_shared, c.I_shared, nullptr, nullptr, T, dense_tiles, stream);

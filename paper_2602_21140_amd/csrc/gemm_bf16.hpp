@@ -65,6 +65,10 @@ struct GemmArgs {
   int b_sel;                 // -1: weights from B_tab / B_one; 0 or 1: from the tile record's w[b_sel]
   int b_tiled;               // B is stored in the tiled weight layout (see kWeightTileRows)
   int b_rows_pad;            // tiled: rows of B (of each half for SwiGLU) padded to whole tiles
+  int a_rows;                // > 0: A is stored K-panel-major, [K/32][a_rows][32]: the 32 K-elements of a row that one
+                             // K-step needs are 64 contiguous bytes and consecutive rows follow each other, so the
+                             // copies of a row-tile read one contiguous run per K-step (used for the intermediate h)
+  int c_rows;                // > 0 (bf16 epilogues): C is written in the same layout, [n_out/32][c_rows][32]
 };
 
 // Up to two independent problems served by one launch (e.g. the routed experts' grouped GEMM and
@@ -411,7 +415,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
     const int chunk = (lane & 3) ^ swz32(row);
     if (isA) {
       const int rrow = min(row, row_end - row_begin - 1);  // rows past the tile re-read its last row
-      cp_off[i] = static_cast<uint32_t>((static_cast<int64_t>(rrow) * g.lda + chunk * 8) * 2);
+      cp_off[i] = g.a_rows > 0 ? static_cast<uint32_t>((rrow * 32 + chunk * 8) * 2)
+                               : static_cast<uint32_t>((static_cast<int64_t>(rrow) * g.lda + chunk * 8) * 2);
       cp_dst[i] = blk * 1024;
     } else {
       if (g.b_tiled) {
@@ -450,12 +455,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
     const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(v)));
     return (static_cast<uint64_t>(hi) << 32) | lo;
   };
-  const uint64_t base_a = uniform64(reinterpret_cast<uint64_t>(Abase) + static_cast<uint64_t>(row_begin) * g.lda * 2);
+  const uint64_t base_a = uniform64(reinterpret_cast<uint64_t>(Abase) + static_cast<uint64_t>(row_begin) * (g.a_rows > 0 ? 32 : g.lda) * 2);
+  const uint64_t kstep_a = g.a_rows > 0 ? static_cast<uint64_t>(g.a_rows) * 64 : 64;
   const uint64_t base_b = uniform64(reinterpret_cast<uint64_t>(Bbase));
   const uint32_t kstep_b = g.b_tiled ? kWeightTileRows * kWeightTileK * 2 : 64;  // bytes between K-steps of B
   auto issue_copy = [&](int kt) {
     const uint32_t stage = smem_lds + stage_of(kt) * STAGE;
-    const uint64_t src_a = base_a + static_cast<uint64_t>(kt) * 64;  // 32 bf16 further along the row
+    const uint64_t src_a = base_a + static_cast<uint64_t>(kt) * kstep_a;
     const uint64_t src_b = base_b + static_cast<uint64_t>(kt) * kstep_b;
 #pragma unroll
     for (int i = 0; i < CP; ++i) {
@@ -659,7 +665,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
       const int row = row_begin + (tm * WAVES_M + wm) * 32 + (lrow & 31);
       if (row < row_end) {
         const u32x4 o = *reinterpret_cast<const u32x4*>(slice + lrow * ROWB + rcol * 2);
-        *reinterpret_cast<u32x4*>(static_cast<uint16_t*>(g.C) + static_cast<int64_t>(row) * g.ldc + col) = o;
+        uint16_t* dst = static_cast<uint16_t*>(g.C);
+        // a 16-byte word is 8 columns inside one 32-column panel
+        if (g.c_rows > 0) dst += (static_cast<int64_t>(col / kWeightTileK) * g.c_rows + row) * kWeightTileK + col % kWeightTileK;
+        else dst += static_cast<int64_t>(row) * g.ldc + col;
+        *reinterpret_cast<u32x4*>(dst) = o;
       }
     }
   }
