@@ -129,7 +129,7 @@ def main():
                          "counters collected over this command can be scaled by a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (expert-parallel ranks are simulated as rank segments "
+        print("bench.py: this library runs on one GPU only (expert-parallel ranks are simulated as rank segments "
               "inside one HBM); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
