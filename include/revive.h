@@ -53,7 +53,8 @@
  *     from and to the math layout.
  *   - Limits: E <= 512, P = n_ranks*slots_per_rank <= 1024, k <= 32,
  *     H % 8 == 0; for bf16 additionally H % 64 == 0, I % 64 == 0 and
- *     I_shared % 64 == 0.
+ *     I_shared % 64 == 0, and one expert matrix (2*I*H or H*I elements, rows
+ *     padded to 128) must stay below 2 GiB.
  */
 #ifndef REVIVE_H
 #define REVIVE_H
