@@ -79,6 +79,7 @@ def cpu_baseline(cfg, g, sample_tokens):
     """Time the oracle (as it stands) on the first `sample_tokens` tokens of the workload."""
     import numpy as np
     import torch
+    import synth
     from oracle import revive_oracle as orc
 
     def f64(t):
@@ -86,16 +87,11 @@ def cpu_baseline(cfg, g, sample_tokens):
 
     x = f64(g.x[:sample_tokens])
     w_r = f64(g.w_router)
-    from paper_2602_21140_amd import unpack_expert
-
-    def math(gu, dn, I):
-        return {n: np.ascontiguousarray(f64(t)) for n, t in zip(("gate", "up", "down"), unpack_expert(gu, dn, cfg.H, I))}
-
-    experts = {}
-    for e in range(cfg.E):
-        p = int(np.nonzero(g.p2l == e)[0][0])
-        experts[e] = math(g.gu[p], g.dn[p], cfg.I)
-    shared = math(g.sh_gate_up, g.sh_down, cfg.I_shared) if g.sh_gate_up is not None else None
+    # the oracle gets the weights from the seeded generator itself (same seed and device: the bits the layer packed)
+    experts = {e: {n: np.ascontiguousarray(f64(t)) for n, t in synth.draw_expert(cfg, e, g.device).items()}
+               for e in range(cfg.E)}
+    sh = synth.draw_shared(cfg, g.device)
+    shared = None if sh is None else {n: np.ascontiguousarray(f64(t)) for n, t in sh.items()}
     emap = orc.build_map(g.p2l, g.failed, cfg.slots_per_rank, cfg.E, cfg.max_replicas)
     t0 = time.perf_counter()
     orc.layer_staged(x, w_r, experts, shared, g.p2l, emap, cfg.k, cfg.score_fn, cfg.n_group, cfg.topk_group)

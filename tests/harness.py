@@ -34,23 +34,20 @@ class GpuLayer(ResidentLayer):
         return orc.build_map(self.p2l, self.failed, c.slots_per_rank, c.E, c.max_replicas,
                              expert_failed=self.expert_failed)
 
-    def _math_f64(self, gu, dn, I) -> Dict[str, np.ndarray]:
-        from paper_2602_21140_amd import unpack_expert
-        g, u, d = unpack_expert(gu, dn, self.cfg.H, I)
-        return {"gate": f64(g), "up": f64(u), "down": f64(d)}
-
+    # The oracle's weights are drawn again from the seeded generator (same seed, same device, hence
+    # the same bits the layer packed), never read back through the library's packers: a mistake in
+    # the packed layout then shows up as a parity failure instead of cancelling out.
     def expert_f64(self, e: int) -> Dict[str, np.ndarray]:
-        """Expert e's matrices in math layout, fp64, read back from the first slot that holds it."""
-        p = int(np.nonzero(self.p2l == e)[0][0])
-        return self._math_f64(self.gu[p], self.dn[p], self.cfg.I)
+        """Expert e's matrices in math layout, fp64."""
+        return {n: f64(t) for n, t in synth.draw_expert(self.cfg, int(e), self.device).items()}
 
     def slot_expert_f64(self, p: int) -> Dict[str, np.ndarray]:
-        return self._math_f64(self.gu[p], self.dn[p], self.cfg.I)
+        """The matrices of the expert that slot p holds."""
+        return self.expert_f64(int(self.p2l[p]))
 
     def shared_f64(self) -> Optional[Dict[str, np.ndarray]]:
-        if self.sh_gate_up is None:
-            return None
-        return self._math_f64(self.sh_gate_up, self.sh_down, self.cfg.I_shared)
+        sh = synth.draw_shared(self.cfg, self.device)
+        return None if sh is None else {n: f64(t) for n, t in sh.items()}
 
 
 def compare_selection(cfg, gpu_top: np.ndarray, sel: np.ndarray, ref_top: np.ndarray, gap_limit=1e-5):
