@@ -153,3 +153,55 @@ def test_dense_ffn_group_rebalancing_on_the_gpu():
         assert rel_err(f64(out), ref) < TOL["bf16"]
     finally:
         L.close()
+
+
+def test_empty_slots_are_never_routed_to_and_can_be_filled_later():
+    """A slot that holds no expert (placement -1: spare capacity for a later role switch, Sec. 3.4)
+    takes no rows and its weight pointers are never followed; once weights are written into it and
+    the placement names it, it serves as one more replica."""
+    cfg = synth.scaled(synth.get_config("c2"), T=1100, H=512, I=320, I_shared=192, E=16, k=4, n_ranks=4,
+                       slots_per_rank=6, max_replicas=3, failed_ranks=(1,), n_unprotected=-1)
+    g = GpuLayer(cfg)
+    try:
+        S = cfg.slots_per_rank
+        spare = [r * S + S - 1 for r in range(cfg.n_ranks)]          # last (redundant) slot of every rank
+        held = {p: int(g.p2l[p]) for p in spare}
+        p2l = g.p2l.copy()
+        p2l[spare] = -1
+        saved = {p: (g.gu[p].clone(), g.dn[p].clone()) for p in spare}
+        for p in spare:
+            g.gu[p].fill_(float("nan"))
+            g.dn[p].fill_(float("nan"))
+        g.layer.set_placement(p2l)
+        g.p2l = p2l
+        g.set_failed(cfg.failed_ranks)
+        experts = {e: g.expert_f64(e) for e in range(cfg.E)}
+        r = g.forward()
+        tr = orc.layer_staged(f64(g.x), None, experts, g.shared_f64(), g.p2l, g.oracle_map(), cfg.k, cfg.score_fn,
+                              cfg.n_group, cfg.topk_group, logits=f64(r["logits"]))
+        assert np.array_equal(_i(r["topk_phys"]), tr.topk_phys)
+        assert not np.isin(_i(r["topk_phys"]), spare).any()
+        offs = _i(r["slot_offsets"])
+        assert all(offs[p + 1] == offs[p] for p in spare)
+        assert torch.isfinite(r["out"].float()).all()
+        assert rel_err(f64(r["out"]), tr.out) < TOL[cfg.dtype]
+        # fill the spare slots of the surviving ranks again and name them in the placement
+        for p in spare:
+            g.gu[p].copy_(saved[p][0])
+            g.dn[p].copy_(saved[p][1])
+        torch.cuda.synchronize()
+        p2l = g.p2l.copy()
+        for p in spare:
+            p2l[p] = held[p]
+        g.layer.set_placement(p2l)
+        g.p2l = p2l
+        g.set_failed(cfg.failed_ranks)
+        r = g.forward()
+        tr = orc.layer_staged(f64(g.x), None, experts, g.shared_f64(), g.p2l, g.oracle_map(), cfg.k, cfg.score_fn,
+                              cfg.n_group, cfg.topk_group, logits=f64(r["logits"]))
+        assert np.array_equal(_i(r["topk_phys"]), tr.topk_phys)
+        live_spares = [p for p in spare if p // S not in cfg.failed_ranks]
+        assert np.isin(_i(r["topk_phys"]), live_spares).any()
+        assert rel_err(f64(r["out"]), tr.out) < TOL[cfg.dtype]
+    finally:
+        g.close()
