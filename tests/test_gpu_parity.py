@@ -270,3 +270,32 @@ def test_graph_replay_matches_eager_across_mask_flips():
                 assert g.layer.graph_exec_id(g.graph) == exec_id
     finally:
         g.close()
+
+
+@pytest.mark.parametrize("name", ["c2m", "c1_big"])
+def test_every_token_picks_the_same_experts(name):
+    """Degenerate routing: identical logits rows send all T tokens to the same k experts, so a few
+    slots receive T rows each (many row-tiles in one group, every other slot empty, one-bin
+    histograms in the dispatch) and ties between equal logits go to the lower expert id."""
+    cfg = SMALL[name]
+    g = GpuLayer(cfg)
+    try:
+        E = cfg.E
+        row = torch.zeros(E, dtype=torch.float32)
+        row[: E // 2] = 1.0                       # a tie among the first half, a tie among the second
+        logits = row.repeat(cfg.T, 1).to(g.device)
+        r = g.forward(logits=logits)
+        tr = orc.layer_staged(f64(g.x), None, _experts_f64(g), g.shared_f64(), g.p2l, g.oracle_map(), cfg.k, cfg.score_fn,
+                              cfg.n_group, cfg.topk_group, logits=f64(logits))
+        live = np.nonzero(g.oracle_map().l2p_count > 0)[0]
+        assert np.array_equal(_i(r["topk_logical"])[0], live[: cfg.k])      # lowest live ids win the ties
+        assert np.array_equal(_i(r["topk_logical"]), tr.topk_logical)
+        assert np.abs(f64(r["topk_weight"]) - 1.0 / cfg.k).max() < 1e-6
+        assert np.array_equal(_i(r["topk_phys"]), tr.topk_phys)
+        assert np.array_equal(_i(r["slot_offsets"]), tr.slot_offsets)
+        assert np.array_equal(_i(r["dst_row"]), tr.dst_row) and np.array_equal(_i(r["src_of"]), tr.src_of)
+        counts = np.diff(tr.slot_offsets)
+        assert counts.max() >= cfg.T // cfg.max_replicas and (counts == 0).sum() >= cfg.P - cfg.k * cfg.max_replicas
+        assert rel_err(f64(r["out"]), tr.out) < TOL[cfg.dtype]
+    finally:
+        g.close()
