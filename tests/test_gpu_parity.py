@@ -299,3 +299,44 @@ def test_every_token_picks_the_same_experts(name):
         assert rel_err(f64(r["out"]), tr.out) < TOL[cfg.dtype]
     finally:
         g.close()
+
+
+def test_out_of_range_slot_ids_drop_the_row():
+    """Boundary behaviour of the ABI, not of the method: a slot id outside [0, P) in a caller's
+    topk_phys drops that routed row: it takes no place in the sort (dst_row = -1) and the combine
+    skips it.  The kept rows sort as if the dropped ones were absent."""
+    cfg = SMALL["c2m"]
+    g = GpuLayer(cfg)
+    try:
+        L, T, k, P, H = g.layer, cfg.T, cfg.k, cfg.P, cfg.H
+        rng = np.random.default_rng(3)
+        phys = rng.integers(0, P, size=(T, k)).astype(np.int32)
+        bad = rng.random((T, k)) < 0.05
+        phys[bad] = np.where(rng.random(bad.sum()) < 0.5, -1, P + 7)
+        d_phys = torch.from_numpy(phys).to(g.device)
+        x_perm, offs, dst, src = L.dispatch(g.x, d_phys, T)
+        flat, keep = phys.ravel(), ~bad.ravel()
+        kept = np.nonzero(keep)[0]
+        ref_offs, ref_dst_kept, ref_src_kept = orc.dispatch_indices(flat[kept], P)   # the oracle on the kept rows alone
+        ref_dst = np.full(T * k, -1, dtype=np.int32)
+        ref_dst[kept] = ref_dst_kept
+        n = kept.size
+        assert np.array_equal(_i(offs), ref_offs) and _i(offs)[-1] == n
+        assert np.array_equal(_i(dst), ref_dst)
+        assert np.array_equal(_i(src)[:n], kept[ref_src_kept])
+        assert torch.equal(x_perm[:n], g.x[torch.from_numpy(kept[ref_src_kept] // k).to(g.device)])
+        # combine: only the kept rows contribute
+        y_perm = g.x.new_zeros(T * k, H)
+        y_perm[:n] = torch.randn(n, H, device=g.device).to(y_perm.dtype)
+        w = torch.rand(T, k, device=g.device, dtype=torch.float32)
+        out = L.combine(y_perm, dst, w, None, T)
+        yp, ww = f64(y_perm), f64(w)
+        ref = np.zeros((T, H))
+        for t in range(T):
+            for j in range(k):
+                d = ref_dst[t * k + j]
+                if d >= 0:
+                    ref[t] += ww[t, j] * yp[d]
+        assert rel_err(f64(out), ref) < TOL[cfg.dtype]
+    finally:
+        g.close()
