@@ -340,3 +340,41 @@ def test_out_of_range_slot_ids_drop_the_row():
         assert rel_err(f64(out), ref) < TOL[cfg.dtype]
     finally:
         g.close()
+
+
+def test_data_path_calls_refuse_bad_arguments_without_launching():
+    """Error behaviour of the boundary: wrong sizes, missing state and null pointers come back as a
+    status with a message; nothing is launched and the context stays usable."""
+    import ctypes as C
+    from paper_2602_21140_amd.binding import ReviveError, ReviveLayer, lib
+    cfg = SMALL["c2m"]
+    L = ReviveLayer(cfg)
+    try:
+        T = cfg.T
+        x = synth.draw_x(cfg, L.device)
+        w_r = synth.draw_router(cfg, L.device).t().contiguous()
+        with pytest.raises(ReviveError) as e:          # no map yet
+            L.route(x, w_r, T)
+        assert e.value.status == -3
+        L.set_placement(synth.make_placement(cfg))
+        L.update_map(synth.failed_mask(cfg))
+        with pytest.raises(ReviveError) as e:          # more tokens than the context was sized for
+            L.route(x, w_r, T + 1)
+        assert e.value.status == -1 and "T_max" in str(e.value)
+        raw = lib()
+        null = C.c_void_p(None)
+        i32 = L.empty(T, cfg.k, dtype=torch.int32)
+        f32 = L.empty(T, cfg.k, dtype=torch.float32)
+        lg = L.empty(T, cfg.E, dtype=torch.float32)
+        rc = raw.revive_route(L._ctx, null, null, lg.data_ptr(), 0, T, i32.data_ptr(), f32.data_ptr(), i32.data_ptr(), null)
+        assert rc == -1                                  # x and w_router missing although logits are not given
+        rc = raw.revive_dispatch(L._ctx, x.data_ptr(), i32.data_ptr(), T, null, null, null, null, null)
+        assert rc == -1
+        rc = raw.revive_combine(L._ctx, null, null, null, null, T, null, null)
+        assert rc == -1
+        assert raw.revive_last_error(L._ctx).decode() != ""
+        # the context still works
+        _, top_l, top_w, top_p = L.route(x, w_r, T)
+        assert int(top_p.min()) >= 0
+    finally:
+        L.close()
