@@ -120,6 +120,10 @@ def main():
     ap.add_argument("--microbatches", type=int, default=0,
                     help="also time the same batch run as this many microbatches on separate streams inside one graph "
                          "(a secondary figure under 'microbatch'; the headline value is always the single batch)")
+    ap.add_argument("--skew", type=float, default=0.0,
+                    help="secondary run under uneven expert load: router column e is scaled by exp(skew * z_e), "
+                         "z_e ~ N(0,1) (0.3 gives slots between a few rows and 2.5 times the mean); the headline "
+                         "workload is the unskewed one")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of 1 GiB (read 1 GiB, write 1 GiB) so that hardware "
                          "counters collected over this command can be scaled by a kernel of known traffic")
@@ -135,6 +139,8 @@ def main():
     from paper_2602_21140_amd.layer import ResidentLayer
 
     cfg = synth.get_config(args.workload)
+    if args.skew != 0.0:
+        cfg = synth.scaled(cfg, router_skew=args.skew)
     torch.cuda.set_device(0)
     g = ResidentLayer(cfg, device="cuda:0")
     L = g.layer
@@ -227,6 +233,12 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # rows per live slot of the step just timed (bench reporting only)
+    off = g.buf["slot_offsets"].cpu().numpy().astype(np.int64)
+    live_slots = np.repeat(~g.failed.astype(bool), cfg.slots_per_rank)
+    rows = np.diff(off)[live_slots]
+    load = {"rows_per_live_slot_min": int(rows.min()), "median": int(np.median(rows)), "max": int(rows.max())}
+
     avg_us = {n: (1e3 * ms / c if c else None) for n, (ms, c) in times.items()}
     dom = "ffn_gate_up"
     # with a shared expert the library serves routed and shared gate/up projections in one launch
@@ -263,13 +275,13 @@ def main():
         "config": {"workload": f"{cfg.name}: T={cfg.T} H={cfg.H} E={cfg.E} top-{cfg.k} I={cfg.I} shared I={cfg.I_shared} "
                                f"{cfg.score_fn}" + (f" {cfg.n_group} groups/top-{cfg.topk_group}" if cfg.n_group > 1 else "")
                                + f", {cfg.n_ranks} simulated ranks x {cfg.slots_per_rank} slots, failed ranks "
-                               f"{list(cfg.failed_ranks)}",
-                   "map": g.stats, "execution": "one captured graph replayed per step" + (", shared expert on a side stream" if ov else "")},
+                               f"{list(cfg.failed_ranks)}" + (f", router columns scaled by exp({cfg.router_skew} z)" if cfg.router_skew else ""),
+                   "map": g.stats, "load": load, "execution": "one captured graph replayed per step" + (", shared expert on a side stream" if ov else "")},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_dma_kernel<256,256,2,4,SwiGLU> (ffn_gate_up)" if cfg.dtype == "bf16" else "gemm_f32_kernel<SwiGLU> (ffn_gate_up)",
                      "achieved": dom_tflops, "peak": peak, "unit": "TFLOP/s", "frac": dom_tflops / peak,
                      "avg_launch_us": avg_us[dom], "flops_per_launch": dom_flops,
                      "launch_covers": "routed experts + shared expert gate/up projections" if merged else "routed experts gate/up projection",
-                     "traffic": stored_traffic(cfg.name)},
+                     "traffic": stored_traffic(cfg.name) if cfg.router_skew == 0.0 else None},
         "stages": stages,
         "remap": {"update_map_host_ms": host_ms, "update_to_first_step_done_ms": first_ms,
                   "minus_steady_step_ms": first_ms - ms_per_step, "routes_avoid_failed_ranks": all(r[2] for r in remap),

@@ -32,6 +32,9 @@ class LayerConfig:
     # the primaries of the failed ranks, minus the last `n_unprotected` of them
     n_unprotected: int = -1   # -1: plain round-robin replicas (no targeting)
     seed: int = 0
+    # skewed expert load: router column e is scaled by exp(router_skew * z_e), z_e ~ N(0, 1), so
+    # that some experts' logits spread wider and win top-k more often (0 = near-uniform load)
+    router_skew: float = 0.0
 
     @property
     def P(self) -> int:

@@ -18,6 +18,7 @@ import torch
 from .configs import LayerConfig
 
 _TENSOR_X, _TENSOR_ROUTER, _TENSOR_SHARED, _TENSOR_LOGITS, _TENSOR_EXPERT0 = 0, 1, 2, 3, 16
+_TENSOR_SKEW = 7  # ids 4..6 belong to the shared expert
 
 
 def work_dtype(cfg: LayerConfig) -> torch.dtype:
@@ -44,8 +45,17 @@ def draw_x(cfg: LayerConfig, device="cpu") -> torch.Tensor:
 
 
 def draw_router(cfg: LayerConfig, device="cpu") -> torch.Tensor:
-    """Router matrix [H, E] in the working dtype."""
-    return _normal(cfg, _TENSOR_ROUTER, (cfg.H, cfg.E), cfg.H ** -0.5, device)
+    """Router matrix [H, E] in the working dtype.
+
+    With `cfg.router_skew` > 0 column e is scaled by exp(router_skew * z_e), z_e ~ N(0, 1): the
+    logits of some experts spread wider than others', so top-k picks them more often and the rows
+    per expert slot become uneven, as under real traffic.
+    """
+    if cfg.router_skew == 0.0:
+        return _normal(cfg, _TENSOR_ROUTER, (cfg.H, cfg.E), cfg.H ** -0.5, device)
+    w = _normal(cfg, _TENSOR_ROUTER, (cfg.H, cfg.E), cfg.H ** -0.5, device, torch.float32)
+    z = _normal(cfg, _TENSOR_SKEW, (cfg.E,), 1.0, device, torch.float32)
+    return (w * torch.exp(cfg.router_skew * z)).to(work_dtype(cfg))
 
 
 def draw_logits(cfg: LayerConfig, device="cpu") -> torch.Tensor:

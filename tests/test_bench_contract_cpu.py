@@ -5,6 +5,7 @@ import os
 import subprocess
 import sys
 
+import numpy as np
 import pytest
 
 import synth
@@ -42,3 +43,18 @@ def test_stored_traffic_is_dropped_when_the_kernel_sources_change(tmp_path, monk
     monkeypatch.setattr(bench, "kernel_source_hash", lambda: "0" * 64)
     assert bench.stored_traffic("c2") is None
     assert bench.stored_traffic("no_such_workload") is None
+
+
+def test_router_skew_changes_only_the_router_and_makes_the_load_uneven():
+    import torch
+    base = synth.scaled(synth.get_config("c2"), T=2048)
+    skew = synth.scaled(base, router_skew=0.5)
+    assert torch.equal(synth.draw_x(base), synth.draw_x(skew))
+    assert torch.equal(synth.draw_expert(base, 3)["up"], synth.draw_expert(skew, 3)["up"])
+    assert torch.equal(synth.draw_router(base), synth.draw_router(synth.scaled(base, router_skew=0.0)))
+
+    def spread(cfg):
+        top = (synth.draw_x(cfg).float() @ synth.draw_router(cfg).float()).topk(cfg.k, dim=1).indices
+        cnt = np.bincount(top.numpy().ravel(), minlength=cfg.E)
+        return cnt.max() / cnt.mean()
+    assert spread(base) < 1.3 and spread(skew) > 2.0

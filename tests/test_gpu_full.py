@@ -15,9 +15,11 @@ from harness import GpuLayer, TOL, compare_selection, f64, rel_err
 
 pytestmark = pytest.mark.gpu
 
-FULL = ["c2", "c3", "c4", "c5"]
+# "+skewS": the same workload under uneven expert load (router columns scaled by exp(S z), slots from
+# no rows at all to several row-tiles)
+FULL = ["c2", "c3", "c4", "c5", "c2+skew0.5"]
 N_SAMPLE_TOKENS = 10
-N_SAMPLE_SLOTS = 3
+N_SAMPLE_SLOTS = 4
 
 
 def _i(t):
@@ -26,8 +28,11 @@ def _i(t):
 
 @pytest.fixture(scope="module", params=FULL)
 def full_layer(request):
-    cfg = synth.get_config(request.param)
-    print(f"building {cfg.name} on the GPU", flush=True)
+    name, _, skew = request.param.partition("+skew")
+    cfg = synth.get_config(name)
+    if skew:
+        cfg = synth.scaled(cfg, router_skew=float(skew))
+    print(f"building {request.param} on the GPU", flush=True)
     g = GpuLayer(cfg)
     # as the benchmark runs it: one graph captured on a stream, routed and shared experts in the same
     # launches, results taken from a replay (the outputs are cleared first so that the replay must write them)
@@ -110,6 +115,8 @@ def test_sampled_values_full(full_layer):
     if two:
         slots.append(int(m.l2p_table[two[0], 1]))
     live = np.nonzero((m.slot_alive == 1) & (counts > 0))[0]
+    if int(np.argmax(counts)) not in slots:
+        slots.append(int(np.argmax(counts)))            # the fullest slot: the most row-tiles
     while len(slots) < N_SAMPLE_SLOTS:
         p = int(rng.choice(live))
         if p not in slots:

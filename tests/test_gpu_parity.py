@@ -37,6 +37,9 @@ SMALL = {
                   n_unprotected=-1),
     "k128": _small("c2", T=600, H=128, I=64, I_shared=128, E=16, k=3, n_ranks=4, slots_per_rank=5, failed_ranks=(),
                    n_unprotected=-1),
+    # uneven expert load (router columns scaled by exp(0.6 z)): slots with no rows next to slots of many row-tiles
+    "c2_skew": _small("c2", T=1500, H=512, I=320, I_shared=192, router_skew=0.6),
+    "c3_skew": _small("c3", T=900, H=512, I=256, I_shared=256, router_skew=0.6),
     # the largest expert count, slot count, top-k and group count the library accepts; ranks 3 and 4 are neighbours,
     # so rank 4's primaries lose both copies (8 lost experts), rank 40 only degrades
     "max": _small("c3", T=300, H=128, I=64, I_shared=64, E=512, k=32, n_ranks=64, slots_per_rank=16, max_replicas=2,
