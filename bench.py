@@ -202,6 +202,7 @@ def main():
             ok = not bool(dead[phys.long()].any().item())
             remap.append(((t1 - t0) * 1e3, (t2 - t0) * 1e3, ok))
         g.set_failed(cfg.failed_ranks, stream=stream)
+        g.replay(stream)   # leave the buffers as the workload's own failure set produces them
         stream.synchronize()
         same_exec = L.graph_exec_id(g.graph) == exec_id
 
