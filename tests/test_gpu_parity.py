@@ -381,3 +381,56 @@ def test_data_path_calls_refuse_bad_arguments_without_launching():
         assert int(top_p.min()) >= 0
     finally:
         L.close()
+
+
+def test_random_sequence_of_map_updates_under_one_graph():
+    """Sec. 3.6: recovery, further failures and add-backs are table updates under one captured graph.
+    A random sequence of failure sets (rank failures and single-expert failures), some applied
+    several in a row without a step in between, some refused because too few experts would stay
+    reachable: after every accepted update the replay matches the oracle under the map in force,
+    after every refused one the previous map is still in force."""
+    cfg = SMALL["c4s"]
+    g = GpuLayer(cfg, failed=[])
+    try:
+        experts = _experts_f64(g)
+        rng = np.random.default_rng(11)
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            g.forward(stream=stream)
+            stream.synchronize()
+            g.capture(stream)
+            exec_id = g.layer.graph_exec_id(g.graph)
+            in_force = (synth.failed_mask(cfg, []), None)
+            accepted = refused = 0
+            for step in range(40):
+                for _ in range(int(rng.integers(1, 4))):          # one to three updates before the next step
+                    n_fail = int(rng.choice([0, 1, 2, 3, 6, 12, 24, 30, 31, cfg.n_ranks]))
+                    ranks = synth.failed_mask(cfg, rng.choice(cfg.n_ranks, size=n_fail, replace=False))
+                    ef = (rng.random(cfg.E) < 0.05).astype(np.uint8) if rng.random() < 0.5 else None
+                    m = orc.build_map(g.p2l, ranks, cfg.slots_per_rank, cfg.E, cfg.max_replicas, expert_failed=ef)
+                    ok = orc.enough_live_experts(m.l2p_count, cfg.k, cfg.n_group, cfg.topk_group)
+                    if ok:
+                        g.set_failed(np.nonzero(ranks)[0], stream=stream, expert_failed=ef)
+                        in_force = (ranks, ef)
+                        accepted += 1
+                    else:
+                        with pytest.raises(Exception):
+                            g.layer.update_map(ranks, stream=stream, expert_failed=ef)
+                        refused += 1
+                g.buf["out"].zero_()
+                g.replay(stream)
+                stream.synchronize()
+                m = orc.build_map(g.p2l, in_force[0], cfg.slots_per_rank, cfg.E, cfg.max_replicas, expert_failed=in_force[1])
+                table, count, alive = g.layer.get_map()
+                assert np.array_equal(count, m.l2p_count) and np.array_equal(table, m.l2p_table)
+                tr = orc.layer_staged(f64(g.x), None, experts, g.shared_f64(), g.p2l, m, cfg.k, cfg.score_fn,
+                                      cfg.n_group, cfg.topk_group, logits=f64(g.buf["logits"]))
+                assert np.array_equal(_i(g.buf["topk_logical"]), tr.topk_logical), step
+                assert np.array_equal(_i(g.buf["topk_phys"]), tr.topk_phys), step
+                assert np.array_equal(_i(g.buf["dst_row"]), tr.dst_row), step
+                assert rel_err(f64(g.buf["out"]), tr.out) < TOL[cfg.dtype], step
+            assert g.layer.graph_exec_id(g.graph) == exec_id
+            print(f"map updates accepted {accepted}, refused {refused}")
+            assert accepted > 20 and refused > 0
+    finally:
+        g.close()
