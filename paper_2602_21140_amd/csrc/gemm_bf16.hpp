@@ -376,14 +376,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   if (g.tiles) {
     // One read of any record of the group tells everything.  Inside one group's block of tiles
     // the column index runs slowest: the row-tiles of a slot that use the same weight columns are
-    // neighbours in launch order and meet in L2.
+    // neighbours in launch order and meet in L2 (up to two row-tiles; see below for more).
     const MTile t = g.tiles[m_idx];
     const int in_group = t.pad >> 16;
     int j = t.pad & 0xFFFF;
     if (in_group > 1) {
       const int r = logical - (m_idx - j) * g.n_col_tiles;
-      n_idx = r / in_group;
-      j = r - n_idx * in_group;
+      if (in_group >= 3) {
+        // three or more row-tiles: column tiles are taken in pairs and inside a pair the row-tile
+        // runs slower than the column, so that a row-tile's activations are needed again by the
+        // very next workgroup instead of in_group workgroups later (by then L2 has dropped them)
+        const int blk = r / (2 * in_group), within = r - blk * 2 * in_group;
+        if (blk * 2 + 1 < g.n_col_tiles) { j = within >> 1; n_idx = blk * 2 + (within & 1); }
+        else { j = within; n_idx = blk * 2; }
+      } else {
+        n_idx = r / in_group;
+        j = r - n_idx * in_group;
+      }
     }
     tile_span(t.group_begin, t.group_end, in_group, j, BM, row_begin, row_end);
     Bbase = static_cast<const unsigned char*>(g.b_sel >= 0 ? t.w[g.b_sel] : (g.B_tab ? g.B_tab[t.group] : g.B_one));
@@ -470,6 +479,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
     }
   };
 
+  // The same with the ring position PH of the destination stage known at compile time.
+  auto issue_copy_at = [&](int kt, auto ph_tag) {
+    constexpr int PH = decltype(ph_tag)::value;
+    const uint64_t src_a = base_a + static_cast<uint64_t>(kt) * kstep_a;
+    const uint64_t src_b = base_b + static_cast<uint64_t>(kt) * kstep_b;
+#pragma unroll
+    for (int i = 0; i < CP; ++i) {
+      const uint32_t dst = __builtin_amdgcn_readfirstlane(smem_lds + cp_dst[i] + PH * STAGE);
+      const uint32_t off = cp_off[i];
+      const uint64_t src = i < CP_A ? src_a : src_b;
+      asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(off), "s"(src), "s"(dst) : "memory", "m0");
+    }
+  };
+
   // ---- per-lane fragment addresses.  32-row sub-tiles are dealt round-robin to the wavefront
   // rows (sub-tile tm*WAVES_M + wm), so a ragged row-tile keeps every wavefront equally busy.
   // Every fragment row of a lane is (a multiple of 32) + lane % 32, so the swizzle term depends on
@@ -482,6 +505,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
     const int sw = ((ks * 2 + (lane >> 5)) ^ swz32(lrow)) << 4;
     a_off[ks] = (wm * 32 + lrow) * 64 + sw;
     b_off[ks] = (BM + (EPI == EPI_SWIGLU ? wn * (WN / 2) : wn * WN) + lrow) * 64 + sw;
+  }
+  // The same bases two stages further on: with the ring position known at compile time every
+  // fragment of every stage is an immediate offset below 64 KiB away from one of the two.
+  int a_off2[2], b_off2[2];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    a_off2[ks] = a_off[ks] + 2 * STAGE;
+    b_off2[ks] = b_off[ks] + 2 * STAGE;
   }
   constexpr int A_STEP = WAVES_M * 32 * 64;  // bytes between a wavefront's successive row sub-tiles
   auto b_imm = [](int tn) {                   // byte offset of column tile tn from the lane's base
@@ -509,6 +540,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
       if (TMV == 0) return;
       const unsigned char* pa = base + a_off[ks];
       const unsigned char* pb = base + b_off[ks];
+#pragma unroll
+      for (int tm = 0; tm < TMV; ++tm) af[tm] = *reinterpret_cast<const bf16x8*>(pa + tm * A_STEP);
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) bfr[tn] = *reinterpret_cast<const bf16x8*>(pb + b_imm(tn));
+    };
+    auto load_frags_at = [&](auto ph_tag, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
+      constexpr int PH = decltype(ph_tag)::value;
+      if (TMV == 0) return;
+      const unsigned char* pa = smem + (PH >= 2 ? a_off2[ks] : a_off[ks]) + (PH & 1) * STAGE;
+      const unsigned char* pb = smem + (PH >= 2 ? b_off2[ks] : b_off[ks]) + (PH & 1) * STAGE;
 #pragma unroll
       for (int tm = 0; tm < TMV; ++tm) af[tm] = *reinterpret_cast<const bf16x8*>(pa + tm * A_STEP);
 #pragma unroll
@@ -547,8 +588,47 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
       mfma_step(af1, bf1);
       __builtin_amdgcn_sched_barrier(0);
     };
+    // Steady-state forms of the two steps (the late group's is described below) for a four-stage
+    // ring, with the ring position PH = kt % 4 known at compile time: stage addresses fold into
+    // immediates and the K loop, unrolled by four, carries no vector ALU instruction at all.
+    auto step_at = [&](int kt, auto ph_tag) {
+      constexpr int PH = decltype(ph_tag)::value;
+      issue_copy_at(kt + D, std::integral_constant<int, (PH + D) & 3>{});
+      load_frags_at(ph_tag, 1, af1, bf1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_step(af0, bf0);
+      __builtin_amdgcn_sched_barrier(0);
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((D - 1) * CP));
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      load_frags_at(std::integral_constant<int, (PH + 1) & 3>{}, 0, af0, bf0);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_step(af1, bf1);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    auto step_late_at = [&](int kt, auto ph_tag) {
+      constexpr int PH = decltype(ph_tag)::value;
+      load_frags_at(ph_tag, 1, af1, bf1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_step(af0, bf0);
+      __builtin_amdgcn_sched_barrier(0);
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((D - 1) * CP));
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      issue_copy_at(kt + D + 1, ph_tag);  // (PH + 4) % 4: into this step's own stage
+      load_frags_at(std::integral_constant<int, (PH + 1) & 3>{}, 0, af0, bf0);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_step(af1, bf1);
+      __builtin_amdgcn_sched_barrier(0);
+    };
     using T = std::true_type;
     using F = std::false_type;
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using P2 = std::integral_constant<int, 2>;
+    using P3 = std::integral_constant<int, 3>;
     // Skewed schedule.  Both wavefronts of a SIMD (w and w + NW/2) would otherwise leave the
     // barrier in lockstep and do their non-MFMA work (copy issue, address arithmetic) at the same
     // time, leaving the matrix pipe idle.  The late group issues its copy right after the barrier
@@ -586,6 +666,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
     if (wave < NW / 2) {
       load_frags(smem, 0, af0, bf0);
       int kt = 0;
+      if constexpr (STAGES == 4)  // kt stays a multiple of four here: ring position = unrolled position
+        for (; kt + D + 3 < KT; kt += 4) { step_at(kt, P0{}); step_at(kt + 1, P1{}); step_at(kt + 2, P2{}); step_at(kt + 3, P3{}); }
       for (; kt + D < KT; ++kt) step(kt, T{}, std::integral_constant<int, VM_STEADY>{}, F{});
       // here kt + D >= KT: the copies of every remaining step are already issued
       if (D >= 4 && kt + 3 < KT) { step(kt, F{}, std::integral_constant<int, 2 * CP>{}, F{}); ++kt; }
@@ -596,6 +678,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
       if (KT > D) issue_copy(D);
       load_frags(smem, 0, af0, bf0);
       int kt = 0;
+      if constexpr (STAGES == 4)
+        for (; kt + D + 4 < KT; kt += 4) { step_late_at(kt, P0{}); step_late_at(kt + 1, P1{}); step_late_at(kt + 2, P2{}); step_late_at(kt + 3, P3{}); }
       for (; kt + D + 1 < KT; ++kt) step_late(kt, T{}, std::integral_constant<int, VM_STEADY>{}, F{});
       tail(step_late, kt);
     }
