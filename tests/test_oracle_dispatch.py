@@ -62,3 +62,27 @@ def test_dispatch_tiny_by_hand():
 def test_dispatch_empty():
     offsets, dst_row, src_of = orc.dispatch_indices(np.zeros((0, 2), np.int32), 4)
     assert offsets.tolist() == [0] * 5 and dst_row.size == 0 and src_of.size == 0
+
+
+def test_dispatch_indices_on_random_slot_lists():
+    """Property check on many random inputs (any slot distribution, empty slots, one slot only):
+    dst_row is the permutation of a stable sort by slot, src_of its inverse, offsets the exclusive
+    scan of the counts; checked against a plain Python bucket fill."""
+    rng = np.random.default_rng(9)
+    for case in range(200):
+        P = int(rng.integers(1, 40))
+        T, k = int(rng.integers(0, 60)), int(rng.integers(1, 5))
+        if case % 7 == 0:
+            phys = np.full((T, k), int(rng.integers(0, P)), dtype=np.int32)      # everything on one slot
+        else:
+            phys = rng.integers(0, P, size=(T, k)).astype(np.int32)
+        offsets, dst_row, src_of = orc.dispatch_indices(phys, P)
+        buckets = [[] for _ in range(P)]
+        for i, p in enumerate(phys.ravel().tolist()):
+            buckets[p].append(i)
+        flat = [i for b in buckets for i in b]
+        assert src_of.tolist() == flat
+        assert offsets.tolist() == np.concatenate([[0], np.cumsum([len(b) for b in buckets])]).tolist()
+        inv = np.empty(T * k, dtype=np.int64)
+        inv[np.array(flat, dtype=np.int64)] = np.arange(T * k)
+        assert dst_row.tolist() == inv.tolist()

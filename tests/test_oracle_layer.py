@@ -158,3 +158,28 @@ def test_dense_ffn_group_rebalancing_is_the_same_remap():
     assert counts[[1, 4]].sum() == 0 and counts[[0, 2, 3, 5]].max() - counts[[0, 2, 3, 5]].min() <= 1
     assert np.allclose(tr.topk_weight, 1.0)
     assert np.allclose(tr.out, orc.swiglu_ffn(x, w["gate"], w["up"], w["down"]), atol=1e-12)
+
+
+def test_grouped_ffn_is_one_textbook_mlp_per_slot():
+    """grouped_expert_ffn: the rows of slot p go through the expert slot p holds, nothing else;
+    empty slots contribute nothing; rows keep their positions (row-order independence)."""
+    rng = np.random.default_rng(5)
+    H, I = 12, 7
+    p2l = np.array([2, 0, 1, 0], dtype=np.int32)               # slot 3 is a second copy of expert 0
+    experts = {e: {"gate": rng.standard_normal((H, I)), "up": rng.standard_normal((H, I)),
+                   "down": rng.standard_normal((I, H))} for e in range(3)}
+    offsets = np.array([0, 3, 3, 8, 10], dtype=np.int32)        # slot 1 is empty
+    x = rng.standard_normal((10, H))
+    y = orc.grouped_expert_ffn(x, offsets, p2l, experts)
+    for p in range(4):
+        a, b = offsets[p], offsets[p + 1]
+        w = experts[int(p2l[p])]
+        g, u = x[a:b] @ w["gate"], x[a:b] @ w["up"]
+        ref = ((g / (1.0 + np.exp(-g))) * u) @ w["down"]         # SwiGLU written out with library matmuls
+        assert np.allclose(y[a:b], ref, rtol=1e-12, atol=1e-12)
+    # permuting the rows inside a slot permutes its outputs identically
+    perm = np.array([2, 0, 1, 7, 3, 6, 4, 5, 9, 8])
+    assert np.allclose(orc.grouped_expert_ffn(x[perm], offsets, p2l, experts), y[perm], rtol=1e-12, atol=1e-12)
+    # a mistake that a plain reading would make: using the slot id as the expert id
+    wrong = orc.grouped_expert_ffn(x, offsets, np.arange(4, dtype=np.int32) % 3, experts)
+    assert not np.allclose(wrong[0:3], y[0:3])
