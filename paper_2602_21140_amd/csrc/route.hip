@@ -284,6 +284,11 @@ int launch_router_gemm(revive_ctx* ctx, const void* x, const void* w, float* log
     a.C = logits; a.ldc = c.E;
     a.n_out = c.E; a.K = c.H;
     a.tiles = nullptr; a.tile_count = nullptr; a.M = T;
+    if (static_cast<int64_t>(ceil_div(T, 128)) * ceil_div(c.E, 128) >= 512) {
+      // enough tiles to fill the chip twice over: wider tiles read x fewer times
+      a.n_col_tiles = ceil_div(c.E, 128);
+      return launch_gemm_bf16<128, 128, 2, 2, EPI_F32, REVIVE_K_ROUTER_GEMM>(ctx, a, ceil_div(T, 128), stream);
+    }
     constexpr int BM = 128, BN = 64;
     a.n_col_tiles = ceil_div(c.E, BN);
     return launch_gemm_bf16<BM, BN, 4, 1, EPI_F32, REVIVE_K_ROUTER_GEMM>(ctx, a, ceil_div(T, BM), stream);
