@@ -139,6 +139,10 @@ def main():
                     help="secondary run under uneven expert load: router column e is scaled by exp(skew * z_e), "
                          "z_e ~ N(0,1) (0.3 gives slots between a few rows and 2.5 times the mean); the headline "
                          "workload is the unskewed one")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="context only: also time the vendor library's dense bf16 GEMM (torch.matmul) on the gate/up "
+                         "projection's shape taken as one dense product, with the same kind of random operands "
+                         "(reported under 'context'; no part of the path uses it)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of 1 GiB (read 1 GiB, write 1 GiB) so that hardware "
                          "counters collected over this command can be scaled by a kernel of known traffic")
@@ -242,6 +246,26 @@ def main():
         micro["tokens_per_s"] = cfg.T / (micro["ms_per_step"] * 1e-3)
         pipe.close()
 
+    context = None
+    if args.vendor_gemm and cfg.dtype == "bf16":
+        M, Kd, Nd = cfg.N, cfg.H, 2 * cfg.I
+        a = torch.randn(M, Kd, device="cuda:0", dtype=torch.bfloat16)
+        b = torch.randn(Nd, Kd, device="cuda:0", dtype=torch.bfloat16) * Kd ** -0.5
+        for _ in range(5):
+            c = a @ b.t()
+        torch.cuda.synchronize()
+        v0, v1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        v0.record()
+        for _ in range(20):
+            c = a @ b.t()
+        v1.record()
+        torch.cuda.synchronize()
+        vms = v0.elapsed_time(v1) / 20
+        context = {"vendor_dense_gemm_TFLOPs": 2.0 * M * Kd * Nd / (vms * 1e-3) / 1e12,
+                   "shape": f"{M} x {Kd} x {Nd} bf16 (all routed rows against one expert's gate/up matrix), random operands",
+                   "note": "what the vendor library's dense GEMM reaches on this GPU and data; not part of the path"}
+        del a, b, c
+
     if args.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)
@@ -305,6 +329,8 @@ def main():
     }
     if micro is not None:
         result["microbatch"] = micro
+    if context is not None:
+        result["context"] = context
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, g, min(args.cpu_sample_tokens, cfg.T))
     g.close()

@@ -545,16 +545,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
 #pragma unroll
       for (int tn = 0; tn < TN; ++tn) bfr[tn] = *reinterpret_cast<const bf16x8*>(pb + b_imm(tn));
     };
-    auto load_frags_at = [&](auto ph_tag, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
-      constexpr int PH = decltype(ph_tag)::value;
-      if (TMV == 0) return;
-      const unsigned char* pa = smem + (PH >= 2 ? a_off2[ks] : a_off[ks]) + (PH & 1) * STAGE;
-      const unsigned char* pb = smem + (PH >= 2 ? b_off2[ks] : b_off[ks]) + (PH & 1) * STAGE;
-#pragma unroll
-      for (int tm = 0; tm < TMV; ++tm) af[tm] = *reinterpret_cast<const bf16x8*>(pa + tm * A_STEP);
-#pragma unroll
-      for (int tn = 0; tn < TN; ++tn) bfr[tn] = *reinterpret_cast<const bf16x8*>(pb + b_imm(tn));
-    };
     auto mfma_step = [&](const bf16x8 (&af)[TM], const bf16x8 (&bfr)[TN]) {
 #pragma unroll
       for (int tm = 0; tm < TMV; ++tm)
@@ -588,39 +578,66 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
       mfma_step(af1, bf1);
       __builtin_amdgcn_sched_barrier(0);
     };
+    // The MFMAs of one half-step with the fragment reads of the next half-step dealt in between
+    // them (one read after each of the first MFMAs; the order is pinned with scheduling groups):
+    // the reads then issue in the shadow of the matrix pipe instead of in a block ahead of it.
+    auto mfma_reads_at = [&](const bf16x8 (&af)[TM], const bf16x8 (&bfr)[TN], auto ph_tag, int ks, bf16x8 (&naf)[TM],
+                             bf16x8 (&nbf)[TN]) {
+      constexpr int PH = decltype(ph_tag)::value;
+      if (TMV == 0) return;
+      const unsigned char* pa = smem + (PH >= 2 ? a_off2[ks] : a_off[ks]) + (PH & 1) * STAGE;
+      const unsigned char* pb = smem + (PH >= 2 ? b_off2[ks] : b_off[ks]) + (PH & 1) * STAGE;
+      constexpr int NR = TMV + TN, NM = TMV * TN;  // reads, MFMAs
+#pragma unroll
+      for (int tm = 0; tm < TMV; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+          acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tn], af[tm], acc[tm][tn], 0, 0, 0);
+          const int idx = tm * TN + tn;
+          if (idx < TMV) naf[idx] = *reinterpret_cast<const bf16x8*>(pa + idx * A_STEP);
+          else if (idx < NR) nbf[idx - TMV] = *reinterpret_cast<const bf16x8*>(pb + b_imm(idx - TMV));
+        }
+#pragma unroll
+      for (int idx = NM; idx < NR; ++idx) {  // fewer MFMAs than reads: the remaining reads follow
+        if (idx < TMV) naf[idx] = *reinterpret_cast<const bf16x8*>(pa + idx * A_STEP);
+        else nbf[idx - TMV] = *reinterpret_cast<const bf16x8*>(pb + b_imm(idx - TMV));
+      }
+      constexpr int PAIRS = NR < NM ? NR : NM;
+#pragma unroll
+      for (int i = 0; i < PAIRS; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+      }
+      if (NM > PAIRS) __builtin_amdgcn_sched_group_barrier(0x008, NM - PAIRS, 0);
+      if (NR > PAIRS) __builtin_amdgcn_sched_group_barrier(0x100, NR - PAIRS, 0);
+    };
     // Steady-state forms of the two steps (the late group's is described below) for a four-stage
     // ring, with the ring position PH = kt % 4 known at compile time: stage addresses fold into
     // immediates and the K loop, unrolled by four, carries no vector ALU instruction at all.
     auto step_at = [&](int kt, auto ph_tag) {
       constexpr int PH = decltype(ph_tag)::value;
       issue_copy_at(kt + D, std::integral_constant<int, (PH + D) & 3>{});
-      load_frags_at(ph_tag, 1, af1, bf1);
       __builtin_amdgcn_sched_barrier(0);
-      mfma_step(af0, bf0);
+      mfma_reads_at(af0, bf0, ph_tag, 1, af1, bf1);
       __builtin_amdgcn_sched_barrier(0);
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((D - 1) * CP));
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      load_frags_at(std::integral_constant<int, (PH + 1) & 3>{}, 0, af0, bf0);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_step(af1, bf1);
+      mfma_reads_at(af1, bf1, std::integral_constant<int, (PH + 1) & 3>{}, 0, af0, bf0);
       __builtin_amdgcn_sched_barrier(0);
     };
     auto step_late_at = [&](int kt, auto ph_tag) {
       constexpr int PH = decltype(ph_tag)::value;
-      load_frags_at(ph_tag, 1, af1, bf1);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_step(af0, bf0);
+      mfma_reads_at(af0, bf0, ph_tag, 1, af1, bf1);
       __builtin_amdgcn_sched_barrier(0);
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((D - 1) * CP));
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
       issue_copy_at(kt + D + 1, ph_tag);  // (PH + 4) % 4: into this step's own stage
-      load_frags_at(std::integral_constant<int, (PH + 1) & 3>{}, 0, af0, bf0);
       __builtin_amdgcn_sched_barrier(0);
-      mfma_step(af1, bf1);
+      mfma_reads_at(af1, bf1, std::integral_constant<int, (PH + 1) & 3>{}, 0, af0, bf0);
       __builtin_amdgcn_sched_barrier(0);
     };
     using T = std::true_type;
