@@ -205,3 +205,64 @@ def test_empty_slots_are_never_routed_to_and_can_be_filled_later():
         assert rel_err(f64(r["out"]), tr.out) < TOL[cfg.dtype]
     finally:
         g.close()
+
+
+def _golden_route_cases():
+    import os
+    from fractions import Fraction
+    path = os.path.join(os.path.dirname(__file__), "golden", "tiny_route.txt")
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, fn, shape, ratios, masked, ids, weights = [f.strip() for f in line.split("|")]
+        n_group, topk_group, k = (int(v) for v in shape.split())
+        yield (name, fn, n_group, topk_group, k, [float(v) for v in ratios.split()],
+               [] if masked == "-" else [int(v) for v in masked.split()],
+               [int(v) for v in ids.split()], [float(Fraction(v)) for v in weights.split()])
+
+
+@pytest.mark.parametrize("case", list(_golden_route_cases()), ids=lambda c: c[0])
+def test_hand_worked_gating_examples_on_the_gpu(case):
+    """The routing kernel against tests/golden/tiny_route.txt (values worked out by hand, no oracle in
+    between): scores, mask before top-k, next-best experts, group-limited selection, weights."""
+    name, fn, n_group, topk_group, k, ratios, masked, ids, weights = case
+    E = len(ratios)
+    cfg = synth.LayerConfig(name, T=3, H=64, E=E, k=k, I=64, I_shared=0, n_ranks=1, slots_per_rank=E, max_replicas=1,
+                            score_fn=fn, n_group=n_group, topk_group=topk_group, dtype="fp32", failed_ranks=())
+    g = GpuLayer(cfg, with_weights=False)
+    try:
+        ef = np.zeros(E, dtype=np.uint8)
+        ef[masked] = 1
+        g.set_failed([], expert_failed=ef)
+        logits = torch.log(torch.tensor([ratios] * cfg.T, dtype=torch.float64)).to(torch.float32).to(g.device)
+        _, top_l, top_w, top_p = g.layer.route(None, None, cfg.T, logits=logits, logits_given=True)
+        for t in range(cfg.T):
+            assert top_l[t].cpu().tolist() == ids
+            assert top_p[t].cpu().tolist() == ids          # one slot per expert, slot id = expert id
+            assert np.allclose(top_w[t].cpu().numpy(), weights, rtol=0, atol=2e-6)
+    finally:
+        g.close()
+
+
+def test_hand_worked_dispatch_example_on_the_gpu():
+    """The dispatch kernels against tests/golden/tiny_dispatch.txt (worked out by hand)."""
+    import os
+    rows = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "tiny_dispatch.txt")):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            key, rest = line.split(None, 1)
+            rows[key] = rest
+    phys = np.array([[int(v) for v in tok.split()] for tok in rows["topk_phys"].split("|")], dtype=np.int32)
+    cfg = synth.LayerConfig("tiny_dispatch", T=4, H=64, E=5, k=2, I=64, I_shared=0, n_ranks=5, slots_per_rank=1,
+                            max_replicas=1, score_fn="softmax", n_group=1, topk_group=1, dtype="fp32", failed_ranks=())
+    g = GpuLayer(cfg, with_weights=False)
+    try:
+        x_perm, offs, dst, src = g.layer.dispatch(g.x, torch.from_numpy(phys).to(g.device), cfg.T)
+        assert offs.cpu().tolist() == [int(v) for v in rows["slot_offsets"].split()]
+        assert src.cpu().tolist() == [int(v) for v in rows["src_of"].split()]
+        assert dst.cpu().tolist() == [int(v) for v in rows["dst_row"].split()]
+        assert torch.equal(x_perm, g.x[torch.tensor([int(v) // cfg.k for v in rows["src_of"].split()], device=g.device)])
+    finally:
+        g.close()

@@ -86,3 +86,19 @@ def test_dispatch_indices_on_random_slot_lists():
         inv = np.empty(T * k, dtype=np.int64)
         inv[np.array(flat, dtype=np.int64)] = np.arange(T * k)
         assert dst_row.tolist() == inv.tolist()
+
+
+def test_hand_worked_dispatch_example():
+    """tests/golden/tiny_dispatch.txt."""
+    import os
+    rows = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "tiny_dispatch.txt")):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            key, rest = line.split(None, 1)
+            rows[key] = rest
+    phys = np.array([[int(v) for v in tok.split()] for tok in rows["topk_phys"].split("|")], dtype=np.int32)
+    offsets, dst_row, src_of = orc.dispatch_indices(phys, 5)
+    assert offsets.tolist() == [int(v) for v in rows["slot_offsets"].split()]
+    assert src_of.tolist() == [int(v) for v in rows["src_of"].split()]
+    assert dst_row.tolist() == [int(v) for v in rows["dst_row"].split()]

@@ -205,3 +205,31 @@ def test_router_logits_transposition_pin():
     x = np.array([[1.0, 2.0, 3.0]])
     w = np.array([[1.0, 0.0], [0.0, 1.0], [1.0, 1.0]])
     assert orc.router_logits(x, w).tolist() == [[4.0, 5.0]]
+
+
+def _golden_route_cases():
+    import os
+    from fractions import Fraction
+    path = os.path.join(os.path.dirname(__file__), "golden", "tiny_route.txt")
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, fn, shape, ratios, masked, ids, weights = [f.strip() for f in line.split("|")]
+        n_group, topk_group, k = (int(v) for v in shape.split())
+        yield (name, fn, n_group, topk_group, k, [float(v) for v in ratios.split()],
+               [] if masked == "-" else [int(v) for v in masked.split()],
+               [int(v) for v in ids.split()], [float(Fraction(v)) for v in weights.split()])
+
+
+@pytest.mark.parametrize("case", list(_golden_route_cases()), ids=lambda c: c[0])
+def test_hand_worked_gating_examples(case):
+    """tests/golden/tiny_route.txt: scores, mask before top-k, next-best experts, groups, weights."""
+    name, fn, n_group, topk_group, k, ratios, masked, ids, weights = case
+    logits = np.log(np.array([ratios]))
+    count = np.ones(len(ratios), dtype=np.int32)
+    count[masked] = 0
+    s = orc.scores(logits, fn)
+    top = orc.select_topk(orc.masked_selection_scores(s, count), k, n_group, topk_group)
+    assert top[0].tolist() == ids
+    assert np.allclose(orc.gate_weights(s, top)[0], weights, rtol=0, atol=1e-12)
