@@ -54,7 +54,9 @@
  *   - Limits: E <= 512, P = n_ranks*slots_per_rank <= 1024, k <= 32,
  *     H % 8 == 0; for bf16 additionally H % 64 == 0, I % 64 == 0 and
  *     I_shared % 64 == 0, and one expert matrix (2*I*H or H*I elements, rows
- *     padded to 128) must stay below 2 GiB.
+ *     padded to 128) must stay below 2 GiB.  T_max * k < 2^30, and T_max * k
+ *     must stay below 32768 row-tiles (256 rows for bf16, 64 rows for fp32),
+ *     the most one slot can be handed when every token picks it.
  */
 #ifndef REVIVE_H
 #define REVIVE_H

@@ -1,6 +1,8 @@
 // Context, map update (recovery step), graph replay and timing of the failure-remapped MoE layer.
 #include <algorithm>
+#include <mutex>
 #include <new>
+#include <utility>
 
 #include "ctx.hpp"
 
@@ -24,6 +26,20 @@ int check_hip(const revive_ctx* ctx, hipError_t e, const char* what) {
 }
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+hipError_t allow_dynamic_lds(const void* kernel, size_t lds) {
+  static std::mutex mu;
+  static std::vector<std::pair<int, const void*>> done;  // (device, kernel) pairs already configured
+  int dev = 0;
+  hipError_t rc = hipGetDevice(&dev);
+  if (rc != hipSuccess) return rc;
+  std::lock_guard<std::mutex> lock(mu);
+  for (const auto& d : done)
+    if (d.first == dev && d.second == kernel) return hipSuccess;
+  rc = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+  if (rc == hipSuccess) done.emplace_back(dev, kernel);
+  return rc;
+}
 
 KernelTimer::KernelTimer(revive_ctx* c, int kernel, hipStream_t s) : ctx(c), stream(s) {
   if (!ctx->timing) return;
@@ -145,6 +161,11 @@ static int check_config(const revive_config& c) {
   if (c.dtype == REVIVE_DTYPE_F32 && (c.I % 4 != 0 || c.I_shared % 4 != 0))
     return fail(nullptr, REVIVE_EINVAL, "config: fp32 needs I and I_shared multiples of 4");
   if (static_cast<int64_t>(c.T_max) * c.k >= (1ll << 30)) return fail(nullptr, REVIVE_EINVAL, "config: T_max * k too large");
+  // a row-tile record keeps the number of row-tiles of its slot and its own position in 16 bits each
+  const int tile_m = c.dtype == REVIVE_DTYPE_BF16 ? kTileM_bf16 : kTileM_f32;
+  if (ceil_div64(static_cast<int64_t>(c.T_max) * c.k, tile_m) >= kMaxTilesPerSlot)
+    return fail(nullptr, REVIVE_EINVAL, "config: T_max * k = %lld routed rows could put %d or more row-tiles of %d rows into one slot",
+                static_cast<long long>(c.T_max) * c.k, kMaxTilesPerSlot, tile_m);
   return REVIVE_OK;
 }
 

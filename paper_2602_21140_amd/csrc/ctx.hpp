@@ -23,6 +23,7 @@ constexpr int kTimingPairs = 8192;    // event pairs kept before timing results 
 // Tile heights of the grouped GEMMs (rows of one slot handled by one workgroup).
 constexpr int kTileM_bf16 = 256;
 constexpr int kTileM_f32 = 64;
+constexpr int kMaxTilesPerSlot = 1 << 15;  // MTile::pad holds count and position in 16 bits each
 
 // One row-tile of a grouped GEMM.  All row-tiles of a group (physical slot) carry the same
 // record except for their position; tile_span() gives the rows of tile j.  The group's weight
@@ -138,7 +139,12 @@ struct KernelTimer {
 };
 int fold_timing(revive_ctx* ctx);
 
+// Raises a kernel's dynamic-LDS limit to `lds` bytes on the current device.  Done once per kernel
+// and device; safe to call from several host threads.
+hipError_t allow_dynamic_lds(const void* kernel, size_t lds);
+
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Upper bound on row-tiles of a grouped GEMM over N rows in at most `groups` non-empty groups.
 inline int max_tiles(int64_t n_rows, int groups, int tile_m) {

@@ -783,12 +783,7 @@ int launch_gemm_bf16(revive_ctx* ctx, const GemmArgs& args, int max_m_tiles, hip
   constexpr int NT = 64 * WAVES_M * WAVES_N;
   constexpr size_t lds = 2 * (BM + BN) * 128;
   auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, EPI, KID>;
-  static bool configured = false;  // per instantiation
-  if (!configured) {
-    REVIVE_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        static_cast<int>(lds)));
-    configured = true;
-  }
+  REVIVE_HIP(ctx, allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
   const int64_t total = static_cast<int64_t>(max_m_tiles) * args.n_col_tiles;
   if (total <= 0) return REVIVE_OK;
   const int grid = static_cast<int>((total + 7) / 8 * 8);
@@ -805,12 +800,7 @@ int launch_gemm_bf16_dma(revive_ctx* ctx, const GemmArgs& p0, int max_m_tiles0, 
   constexpr size_t lds_ring = STAGES * (BM + BN) * 64;
   constexpr size_t lds = lds_ring > lds_epi ? lds_ring : lds_epi;
   auto kern = gemm_bf16_dma_kernel<BM, BN, WAVES_M, WAVES_N, EPI, KID, STAGES>;
-  static bool configured = false;  // per instantiation
-  if (!configured) {
-    REVIVE_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        static_cast<int>(lds)));
-    configured = true;
-  }
+  REVIVE_HIP(ctx, allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
   GemmArgs2 a{};
   a.p0 = p0;
   a.two = p1 != nullptr;

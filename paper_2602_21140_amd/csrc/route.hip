@@ -39,15 +39,15 @@ __global__ __launch_bounds__(256) void route_topk_kernel(RouteParams p) {
 
   float key[VALS];
   const float* row = p.logits + static_cast<int64_t>(t) * p.E;
-  float vmax = NEG;  // largest logit of the row, masked or not: common shift of the exponentials
+  float vmax = NEG;  // largest live logit of the row: common shift of the exponentials (the best chosen score is exactly 1)
 #pragma unroll
   for (int i = 0; i < VALS; ++i) {
     const int e = lane + 64 * i;
     float z = NEG;
     if (e < p.E) {
       z = row[e];
-      vmax = fmaxf(vmax, z);
       if (p.l2p_count[e] <= 0) z = NEG;  // failure mask
+      vmax = fmaxf(vmax, z);
     }
     key[i] = z;
   }
@@ -247,12 +247,7 @@ template <int NTN, int KS>
 int launch_router_direct(revive_ctx* ctx, const void* x, const void* w, float* logits, int T, hipStream_t stream) {
   constexpr size_t lds = static_cast<size_t>(KS - 1) * NTN * 16 * 64 * sizeof(float);
   auto kern = router_direct_kernel<NTN, KS>;
-  static bool configured = false;
-  if (!configured) {
-    REVIVE_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        static_cast<int>(lds)));
-    configured = true;
-  }
+  REVIVE_HIP(ctx, allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
   hipLaunchKernelGGL(kern, dim3(ceil_div(T, 32), ceil_div(ctx->cfg.E, NTN * 32)), dim3(64 * KS), lds, stream, static_cast<const uint16_t*>(x),
                      static_cast<const uint16_t*>(w), logits, T, ctx->cfg.E, ctx->cfg.H);
   return check_hip(ctx, hipGetLastError(), "router_direct launch");
