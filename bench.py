@@ -8,7 +8,8 @@ from one captured graph.  Prints one JSON line:
   value        tokens/s of the layer (T / mean step time), inputs resident in HBM
   roofline     the dominant kernel (grouped gate/up GEMM of the routed experts) against the bf16
                dense MFMA peak, from HIP-event timing of that kernel inside this run
-  cpu_baseline the CPU oracle timed on this host on a bounded sample of the same workload
+  cpu_baseline the CPU oracle timed on this host on a bounded sample of the same workload (the same switch,
+               --no-cpu-baseline, also drops the oracle check of the remap block: nothing else here uses the oracle)
   stages       per-kernel mean microseconds (one HIP-event pair per launch) and the stage rates (GB/s,
                TFLOP/s) from events recorded between the stages of the same eager step
   remap        latency from revive_update_map to the end of the first step under the new map,
@@ -121,12 +122,53 @@ def cpu_baseline(cfg, g, sample_tokens):
                       f"{cfg.E} experts' weights, combine), {dt:.2f} s"}
 
 
+def check_against_oracle(cfg, g, n_tokens, n_out_tokens, seed):
+    """Is the step that has just run the layer under the map now in force?  Compares, for sampled tokens, the
+    chosen experts and slots with the oracle's selection and remap under that map (on the step's own logits),
+    and for a few of them the complete output row with the oracle's fp64 layer."""
+    import numpy as np
+    import torch
+    import synth
+    from oracle import revive_oracle as orc
+
+    def f64(t):
+        return t.detach().to(torch.float64).cpu().numpy()
+
+    rng = np.random.default_rng(seed)
+    toks = np.sort(rng.choice(cfg.T, size=min(n_tokens, cfg.T), replace=False))
+    idx = torch.from_numpy(toks).to(g.device)
+    b = g.buf
+    m = orc.build_map(g.p2l, g.failed, cfg.slots_per_rank, cfg.E, cfg.max_replicas)
+    s = orc.scores(f64(b["logits"][idx]), cfg.score_fn)
+    ref_l = orc.select_topk(orc.masked_selection_scores(s, m.l2p_count), cfg.k, cfg.n_group, cfg.topk_group)
+    ref_p = np.stack([[m.l2p_table[e, t % m.l2p_count[e]] for e in row] for t, row in zip(toks, ref_l)])
+    ok = bool(np.array_equal(b["topk_logical"][idx].cpu().numpy(), ref_l) and
+              np.array_equal(b["topk_phys"][idx].cpu().numpy(), ref_p))
+    err = None
+    if ok and n_out_tokens > 0:
+        sub = np.arange(min(n_out_tokens, len(toks)))
+        w = orc.gate_weights(s[sub], ref_l[sub])
+        xs = f64(g.x[idx[sub]])
+        ref = np.zeros((len(sub), cfg.H))
+        for a in sub:
+            for j in range(cfg.k):
+                we = {n: f64(t) for n, t in synth.draw_expert(cfg, int(ref_l[a, j]), g.device).items()}
+                ref[a] += w[a, j] * orc.swiglu_ffn(xs[a:a + 1], we["gate"], we["up"], we["down"])[0]
+        sh = synth.draw_shared(cfg, g.device)
+        if sh is not None:
+            ref += orc.swiglu_ffn(xs, f64(sh["gate"]), f64(sh["up"]), f64(sh["down"]))
+        err = float(np.abs(f64(b["out"][idx[sub]]) - ref).max() / np.abs(ref).max())
+        ok = ok and err < (1e-2 if cfg.dtype == "bf16" else 1e-4)
+    return ok, err
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2", help="c2 (default, the metric's configuration), c3, c4, c5, c1")
+    ap.add_argument("--workload", default="c5",
+                    help="c5 (default: the largest of the workloads, which one GPU holds), c4, c3, c2, c1")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--overlap-shared", action="store_true",
@@ -219,7 +261,12 @@ def main():
             phys = g.buf["topk_phys"]
             dead = torch.from_numpy(np.repeat(g.failed, cfg.slots_per_rank)).to(phys.device)
             ok = not bool(dead[phys.long()].any().item())
-            remap.append(((t1 - t0) * 1e3, (t2 - t0) * 1e3, ok))
+            # outside the timed region: that first step against the oracle under the new map (every trial the
+            # routing of sampled tokens, the first two trials also complete output rows)
+            match, err = (None, None)
+            if not args.no_cpu_baseline:
+                match, err = check_against_oracle(cfg, g, 256, 2 if trial < 2 else 0, seed=100 + trial)
+            remap.append(((t1 - t0) * 1e3, (t2 - t0) * 1e3, ok, match, err))
         g.set_failed(cfg.failed_ranks, stream=stream)
         g.replay(stream)   # leave the buffers as the workload's own failure set produces them
         stream.synchronize()
@@ -325,6 +372,8 @@ def main():
         "stages": stages,
         "remap": {"update_map_host_ms": host_ms, "update_to_first_step_done_ms": first_ms,
                   "minus_steady_step_ms": first_ms - ms_per_step, "routes_avoid_failed_ranks": all(r[2] for r in remap),
+                  "first_step_matches_oracle_under_new_map": (None if args.no_cpu_baseline else all(r[3] for r in remap)),
+                  "first_step_out_rel_err": [r[4] for r in remap if r[4] is not None],
                   "same_graph_exec": same_exec},
     }
     if micro is not None:

@@ -98,7 +98,8 @@ class ResidentLayer:
         if logits is None:
             L.route(self.x, self.w_router_packed, T, logits=b["logits"], out=out3, stream=main)
         else:
-            b["logits"].copy_(logits)
+            with torch.cuda.stream(main):      # ordered before the gate on the stream the gate runs on (and recorded by a capture of it)
+                b["logits"].copy_(logits)
             L.route(None, None, T, logits=b["logits"], logits_given=True, out=out3, stream=main)
         mark()
         L.dispatch(self.x, b["topk_phys"], T, out=(b["x_perm"], b["slot_offsets"], b["dst_row"], b["src_of"]), stream=main)
