@@ -235,6 +235,21 @@ int revive_dispatch(revive_ctx* ctx, const void* x, const int32_t* topk_phys, in
                     void* x_perm, int32_t* slot_offsets, int32_t* dst_row, int32_t* src_of,
                     revive_stream stream);
 
+/* revive_dispatch for callers that cannot allocate or bind device memory (code
+ * under graph capture set up by someone else, serving loops and harnesses that
+ * forbid hipMalloc): same arguments, same results, but the kernels' scratch
+ * (chunk histograms and the finished-workgroup counter) is a static device
+ * array inside the library instead of the bound workspace, so no workspace
+ * is needed and the call allocates nothing.  The array is 256 KiB + 256 B, is
+ * held by every GPU the library is loaded on until the process ends, and bounds
+ * the call to T * k <= 65536 routed rows (REVIVE_EINVAL beyond that; P <= 1024
+ * as everywhere).  All contexts of a device share the one array: calls of this
+ * entry point that overlap in time on one GPU race, whatever their streams.
+ * Capturable like revive_dispatch. */
+int revive_dispatch_static(revive_ctx* ctx, const void* x, const int32_t* topk_phys, int32_t T,
+                           void* x_perm, int32_t* slot_offsets, int32_t* dst_row, int32_t* src_of,
+                           revive_stream stream);
+
 /* a8 - Expert FFN (Sec. 2.1): for every slot p with rows [slot_offsets[p],
  * slot_offsets[p+1]):  y = (silu(X G_p) * (X U_p)) D_p, and the same on all T
  * rows of x for the shared expert when y_shared != NULL.

@@ -79,6 +79,7 @@ def lib() -> C.CDLL:
         "revive_build_map": (C.c_int, [P(Config), vp, vp, vp, vp, vp, P(MapStats)]),
         "revive_route": (C.c_int, [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]),
         "revive_dispatch": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp, vp]),
+        "revive_dispatch_static": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp, vp]),
         "revive_expert_ffn": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]),
         "revive_shared_ffn": (C.c_int, [vp, vp, vp, vp, vp, i32, vp]),
         "revive_combine": (C.c_int, [vp, vp, vp, vp, vp, i32, vp, vp]),
@@ -105,7 +106,7 @@ def lib() -> C.CDLL:
 EXPORTS = ["revive_create", "revive_destroy", "revive_workspace_bytes", "revive_bind_workspace",
            "revive_set_placement", "revive_update_map", "revive_update_map_experts", "revive_get_map", "revive_build_map",
            "revive_build_map_experts", "revive_compact_ranks", "revive_mask_every_nth", "revive_mask_most_activated", "revive_expert_counts",
-           "revive_route", "revive_dispatch", "revive_expert_ffn", "revive_shared_ffn", "revive_combine",
+           "revive_route", "revive_dispatch", "revive_dispatch_static", "revive_expert_ffn", "revive_shared_ffn", "revive_combine",
            "revive_graph_begin", "revive_graph_end", "revive_graph_launch", "revive_graph_exec_id",
            "revive_graph_destroy", "revive_set_kernel_timing", "revive_kernel_time",
            "revive_reset_kernel_times", "revive_kernel_name", "revive_last_error", "revive_status_name"]
@@ -342,13 +343,17 @@ class ReviveLayer:
                                         _ptr(top_l), _ptr(top_w), _ptr(top_p), self._stream(stream)))
         return logits, top_l, top_w, top_p
 
-    def dispatch(self, x, topk_phys, T: int, out=None, stream=None):
+    def dispatch(self, x, topk_phys, T: int, out=None, stream=None, static_scratch=False):
+        """revive_dispatch, or with static_scratch revive_dispatch_static (which needs `out`: it is
+        for callers that allocate nothing)."""
         N = T * self.cfg.k
         if out is None:
+            assert not static_scratch, "the allocation-free entry point takes caller-owned outputs"
             out = (self.empty(N, self.cfg.H), self.empty(self.P + 1, dtype=torch.int32),
                    self.empty(N, dtype=torch.int32), self.empty(N, dtype=torch.int32))
         x_perm, slot_offsets, dst_row, src_of = out
-        self._check(self.L.revive_dispatch(self._ctx, _ptr(x), _ptr(topk_phys), T, _ptr(x_perm), _ptr(slot_offsets),
+        fn = self.L.revive_dispatch_static if static_scratch else self.L.revive_dispatch
+        self._check(fn(self._ctx, _ptr(x), _ptr(topk_phys), T, _ptr(x_perm), _ptr(slot_offsets),
                                            _ptr(dst_row), _ptr(src_of), self._stream(stream)))
         return x_perm, slot_offsets, dst_row, src_of
 

@@ -224,6 +224,7 @@ int revive_create(const revive_config* cfg, revive_ctx** out) {
     rc = check_hip(nullptr, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_stage[i]), m.bytes, hipHostMallocDefault), "hipHostMalloc");
     if (rc == REVIVE_OK) rc = check_hip(nullptr, hipEventCreateWithFlags(&ctx->stage_done[i], hipEventDisableTiming), "hipEventCreate");
   }
+  if (rc == REVIVE_OK) rc = init_static_dispatch_scratch(nullptr);
   if (rc != REVIVE_OK) {
     revive_destroy(ctx);
     return rc;
@@ -409,6 +410,15 @@ int revive_dispatch(revive_ctx* ctx, const void* x, const int32_t* topk_phys, in
   if (!slot_offsets) return fail(ctx, REVIVE_EINVAL, "revive_dispatch: null slot_offsets");
   if (T > 0 && (!x || !topk_phys || !x_perm || !dst_row || !src_of)) return fail(ctx, REVIVE_EINVAL, "revive_dispatch: null argument");
   return launch_dispatch(ctx, x, topk_phys, T, x_perm, slot_offsets, dst_row, src_of, static_cast<hipStream_t>(stream));
+}
+
+int revive_dispatch_static(revive_ctx* ctx, const void* x, const int32_t* topk_phys, int32_t T, void* x_perm,
+                           int32_t* slot_offsets, int32_t* dst_row, int32_t* src_of, revive_stream stream) {
+  int rc = check_call(ctx, "revive_dispatch_static", T, false);
+  if (rc != REVIVE_OK) return rc;
+  if (!slot_offsets) return fail(ctx, REVIVE_EINVAL, "revive_dispatch_static: null slot_offsets");
+  if (T > 0 && (!x || !topk_phys || !x_perm || !dst_row || !src_of)) return fail(ctx, REVIVE_EINVAL, "revive_dispatch_static: null argument");
+  return launch_dispatch_static(ctx, x, topk_phys, T, x_perm, slot_offsets, dst_row, src_of, static_cast<hipStream_t>(stream));
 }
 
 int revive_expert_ffn(revive_ctx* ctx, const void* x_perm, const int32_t* slot_offsets, const void* const* w_gate_up,

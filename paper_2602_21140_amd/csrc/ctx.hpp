@@ -18,6 +18,7 @@ constexpr int kMaxE = 512;
 constexpr int kMaxP = 1024;
 constexpr int kMaxK = 32;
 constexpr int kDispatchChunk = 1024;  // routed rows handled by one block of the count/place kernels
+constexpr int kStaticDispatchChunks = 64;  // chunks the statically allocated dispatch scratch holds (65536 routed rows)
 constexpr int kTimingPairs = 8192;    // event pairs kept before timing results are folded
 
 // Tile heights of the grouped GEMMs (rows of one slot handled by one workgroup).
@@ -157,6 +158,9 @@ int launch_route_topk(revive_ctx*, const float* logits, int T, int32_t* topk_log
                       int32_t* topk_phys, hipStream_t);
 int launch_dispatch(revive_ctx*, const void* x, const int32_t* topk_phys, int T, void* x_perm,
                     int32_t* slot_offsets, int32_t* dst_row, int32_t* src_of, hipStream_t);
+int init_static_dispatch_scratch(revive_ctx*);  // looks up this device's copy of the static scratch, once per device
+int launch_dispatch_static(revive_ctx*, const void* x, const int32_t* topk_phys, int T, void* x_perm,
+                           int32_t* slot_offsets, int32_t* dst_row, int32_t* src_of, hipStream_t);
 int launch_expert_ffn(revive_ctx*, const void* x_perm, const int32_t* slot_offsets, const void* const* w_gate_up,
                       const void* const* w_down, void* y_perm, const void* x, const void* w_sh_gate_up,
                       const void* w_sh_down, void* y_shared, int T, hipStream_t);

@@ -13,6 +13,8 @@
 //   permute  one workgroup per token: destination of each of its k routed rows = slot offset +
 //            chunk base + rank in the chunk (-> dst_row, src_of), then the row is read once and
 //            written to its k destinations
+#include <mutex>
+
 #include "ctx.hpp"
 
 namespace revive {
@@ -168,14 +170,13 @@ __global__ __launch_bounds__(kThreads) void dispatch_permute_kernel(const uint4*
 
 }  // namespace
 
-int launch_dispatch(revive_ctx* ctx, const void* x, const int32_t* topk_phys, int T, void* x_perm, int32_t* slot_offsets,
-                    int32_t* dst_row, int32_t* src_of, hipStream_t stream) {
+// The two dispatch kernels with their scratch (chunk histograms, ticket) at the given addresses.
+static int run_dispatch(revive_ctx* ctx, const void* x, const int32_t* topk_phys, int T, void* x_perm, int32_t* slot_offsets,
+                        int32_t* dst_row, int32_t* src_of, int32_t* block_hist, unsigned int* ticket, hipStream_t stream) {
   const revive_config& c = ctx->cfg;
   const int P = ctx->P;
   const int N = T * c.k;
   const int n_chunks = ceil_div(N, kChunk);
-  int32_t* block_hist = reinterpret_cast<int32_t*>(ctx->d_ws + ctx->ws.off_block_hist);
-  unsigned int* ticket = reinterpret_cast<unsigned int*>(ctx->d_ws + ctx->ws.off_ticket);
   int nbits = 1;
   while ((1 << nbits) < P) ++nbits;
   {
@@ -193,6 +194,70 @@ int launch_dispatch(revive_ctx* ctx, const void* x, const int32_t* topk_phys, in
     REVIVE_HIP(ctx, hipGetLastError());
   }
   return REVIVE_OK;
+}
+
+int launch_dispatch(revive_ctx* ctx, const void* x, const int32_t* topk_phys, int T, void* x_perm, int32_t* slot_offsets,
+                    int32_t* dst_row, int32_t* src_of, hipStream_t stream) {
+  return run_dispatch(ctx, x, topk_phys, T, x_perm, slot_offsets, dst_row, src_of,
+                      reinterpret_cast<int32_t*>(ctx->d_ws + ctx->ws.off_block_hist),
+                      reinterpret_cast<unsigned int*>(ctx->d_ws + ctx->ws.off_ticket), stream);
+}
+
+// ---- dispatch without any allocation: the scratch is a static device array ---------------------
+//
+// For callers that cannot allocate or bind a workspace.  The array lives in every GPU the library
+// is loaded on until the process ends; each device has its own copy at its own address, which is
+// looked up once per device (the array's name itself is not a device address in host code).
+
+namespace {
+
+constexpr size_t kStaticHistBytes = sizeof(int32_t) * static_cast<size_t>(kStaticDispatchChunks) * kMaxP;
+constexpr size_t kStaticTicketOffset = kStaticHistBytes;  // a multiple of 256
+constexpr size_t kStaticScratchBytes = kStaticHistBytes + 256;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+unsigned char* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+__global__ void clear_word_kernel(unsigned int* word) { *word = 0u; }
+
+}  // namespace
+
+int init_static_dispatch_scratch(revive_ctx* ctx) {
+  int dev = 0;
+  REVIVE_HIP(ctx, hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(ctx, REVIVE_EINVAL, "device %d: more devices than the library keeps scratch pointers for", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (g_scratch_ptr[dev]) return REVIVE_OK;
+  void* p = nullptr;
+  REVIVE_HIP(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+  if (!p) return fail(ctx, REVIVE_EHIP, "hipGetSymbolAddress returned a null address for the dispatch scratch");
+  g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+  return REVIVE_OK;
+}
+
+int launch_dispatch_static(revive_ctx* ctx, const void* x, const int32_t* topk_phys, int T, void* x_perm, int32_t* slot_offsets,
+                           int32_t* dst_row, int32_t* src_of, hipStream_t stream) {
+  const int64_t N = static_cast<int64_t>(T) * ctx->cfg.k;
+  if (N > static_cast<int64_t>(kStaticDispatchChunks) * kChunk)
+    return fail(ctx, REVIVE_EINVAL, "revive_dispatch_static: T * k = %lld routed rows, the static scratch holds at most %d",
+                static_cast<long long>(N), kStaticDispatchChunks * kChunk);
+  int dev = 0;
+  REVIVE_HIP(ctx, hipGetDevice(&dev));
+  unsigned char* base = nullptr;  // this device's copy of the array (never the array's name: that is a host-side stand-in)
+  if (dev >= 0 && dev < kMaxDevices) {
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    base = g_scratch_ptr[dev];
+  }
+  if (!base) return fail(ctx, REVIVE_ESTATE, "revive_dispatch_static: no context has been created on device %d", dev);
+  unsigned int* ticket = reinterpret_cast<unsigned int*>(base + kStaticTicketOffset);
+  // the array keeps whatever the previous call left: the ticket must start at zero (a fill kernel,
+  // not a memset node, so that the call can be recorded into a graph); the histograms are
+  // overwritten before they are read
+  hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, stream, ticket);
+  REVIVE_HIP(ctx, hipGetLastError());
+  return run_dispatch(ctx, x, topk_phys, T, x_perm, slot_offsets, dst_row, src_of, reinterpret_cast<int32_t*>(base), ticket, stream);
 }
 
 }  // namespace revive
