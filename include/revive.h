@@ -193,10 +193,30 @@ int revive_expert_counts(revive_ctx* ctx, const int32_t* topk_logical, int32_t T
  * Without a role switch (switched_device < 0) the device holding the next rank
  * takes the failed one's rank and every later rank is decremented.  With a role
  * switch, switched_device takes the failed device's rank and the gap it leaves
- * behind (if it had a rank) is closed the same way.  Pure host function; on this
- * one-GPU build the rank-segmented buffers need no compaction (a failed rank's
- * segment is simply empty), so nothing on the data path consumes the result. */
+ * behind (if it had a rank) is closed the same way.  Pure host function, one
+ * failure at a time, for a caller that renumbers a communicator. */
 int revive_compact_ranks(int32_t* logical_rank /*host*/, int32_t n, int32_t failed_device, int32_t switched_device);
+
+/* The same renumbering for the simulated ranks of a context, as device-resident
+ * data: revive_update_map keeps, next to the expert map and updated by the same
+ * copy, logical_rank[R] (compacted logical rank of each rank, -1 = failed; the
+ * survivors keep their order, which is what removing the failed ranks one at a
+ * time gives) and the number of live ranks.  A rank that comes back (role
+ * switch into a failed rank's place: its slots are refilled and the rank is
+ * un-failed) takes the failed rank's logical rank again.  revive_get_rank_map
+ * copies the host-side table: logical_rank host int32[R], n_live_ranks host
+ * int32[1]; either may be NULL. */
+int revive_get_rank_map(const revive_ctx* ctx, int32_t* logical_rank /*host*/, int32_t* n_live_ranks /*host*/);
+
+/* Compacted rank segments of a dispatched buffer (Sec. 3.5: after recovery the
+ * failed ranks are no part of the layout).  slot_offsets: dev int32[P+1] as
+ * written by revive_dispatch.  rank_offsets: dev int32[R+1]; for l < n_live,
+ * rank_offsets[l] is the first row of the rank that holds logical rank l, so
+ * that segment l is rows [rank_offsets[l], rank_offsets[l+1]); entries n_live
+ * .. R hold N.  Failed ranks receive no rows, so the segments tile [0, N).
+ * Reads the device-resident rank table: asynchronous on `stream`, allocates
+ * nothing, capturable; a replay after revive_update_map sees the new table. */
+int revive_rank_offsets(revive_ctx* ctx, const int32_t* slot_offsets, int32_t* rank_offsets, revive_stream stream);
 
 /* ---- data path ---------------------------------------------------------- */
 

@@ -159,6 +159,26 @@ def compact_ranks(logical_rank: Sequence[int], failed_device: int, switched_devi
     return ranks
 
 
+def compacted_rank_offsets(slot_offsets: Sequence[int], logical_rank: Sequence[int], slots_per_rank: int) -> List[int]:
+    """Segment boundaries of a dispatched buffer in compacted rank order (Sec. 3.5).
+
+    Device d owns slots [d*S, (d+1)*S), i.e. rows [slot_offsets[d*S], slot_offsets[(d+1)*S]).
+    Entry l (l < number of live devices) is the first row of the device whose logical
+    rank is l; entries from the number of live devices up to len(logical_rank) hold N.
+    A device without a logical rank must have received no rows.
+    """
+    R, S = len(logical_rank), slots_per_rank
+    N = int(slot_offsets[R * S])
+    out = [N] * (R + 1)
+    for d in range(R):
+        a, b = int(slot_offsets[d * S]), int(slot_offsets[(d + 1) * S])
+        if logical_rank[d] < 0:
+            assert a == b, "a device outside the domain holds rows"
+        else:
+            out[logical_rank[d]] = a
+    return out
+
+
 def enough_live_experts(l2p_count: np.ndarray, k: int, n_group: int, topk_group: int) -> bool:
     """True when every token can always be given k live experts.
 

@@ -79,6 +79,8 @@ def lib() -> C.CDLL:
         "revive_build_map": (C.c_int, [P(Config), vp, vp, vp, vp, vp, P(MapStats)]),
         "revive_route": (C.c_int, [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]),
         "revive_dispatch": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp, vp]),
+        "revive_get_rank_map": (C.c_int, [vp, vp, vp]),
+        "revive_rank_offsets": (C.c_int, [vp, vp, vp, vp]),
         "revive_dispatch_static": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp, vp]),
         "revive_expert_ffn": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]),
         "revive_shared_ffn": (C.c_int, [vp, vp, vp, vp, vp, i32, vp]),
@@ -106,6 +108,7 @@ def lib() -> C.CDLL:
 EXPORTS = ["revive_create", "revive_destroy", "revive_workspace_bytes", "revive_bind_workspace",
            "revive_set_placement", "revive_update_map", "revive_update_map_experts", "revive_get_map", "revive_build_map",
            "revive_build_map_experts", "revive_compact_ranks", "revive_mask_every_nth", "revive_mask_most_activated", "revive_expert_counts",
+           "revive_get_rank_map", "revive_rank_offsets",
            "revive_route", "revive_dispatch", "revive_dispatch_static", "revive_expert_ffn", "revive_shared_ffn", "revive_combine",
            "revive_graph_begin", "revive_graph_end", "revive_graph_launch", "revive_graph_exec_id",
            "revive_graph_destroy", "revive_set_kernel_timing", "revive_kernel_time",
@@ -313,6 +316,20 @@ class ReviveLayer:
         alive = np.zeros(self.P, dtype=np.uint8)
         self._check(self.L.revive_get_map(self._ctx, table.ctypes.data, count.ctypes.data, alive.ctypes.data))
         return table, count, alive
+
+    def get_rank_map(self):
+        """(logical_rank int32[R], n_live_ranks) of the map in force (host copies)."""
+        lr = np.zeros(self.cfg.n_ranks, dtype=np.int32)
+        n = C.c_int32()
+        self._check(self.L.revive_get_rank_map(self._ctx, lr.ctypes.data, C.byref(n)))
+        return lr, int(n.value)
+
+    def rank_offsets(self, slot_offsets, out=None, stream=None):
+        """revive_rank_offsets: int32[R+1] compacted rank segment boundaries of a dispatched buffer."""
+        if out is None:
+            out = self.empty(self.cfg.n_ranks + 1, dtype=torch.int32)
+        self._check(self.L.revive_rank_offsets(self._ctx, _ptr(slot_offsets), _ptr(out), self._stream(stream)))
+        return out
 
     # -- weights ---------------------------------------------------------------------------
     def set_expert_weights(self, w_gate_up: Sequence[Optional[torch.Tensor]], w_down: Sequence[Optional[torch.Tensor]]):

@@ -132,6 +132,16 @@ static int build_tables(const revive_ctx* who, const revive_config& c, const int
   return REVIVE_OK;
 }
 
+// Logical ranks after every failed rank has left the communication domain (Sec. 3.5): a failed
+// rank holds no logical rank (-1) and every rank behind it moves down by one for each failed rank
+// in front of it, the relative order of the survivors kept.  Removing the failed ranks one at a
+// time with revive_compact_ranks gives the same table in whatever order they are taken.
+static void compacted_ranks(const uint8_t* rank_failed, int R, int32_t* logical_rank, int32_t* n_live) {
+  int next = 0;
+  for (int r = 0; r < R; ++r) logical_rank[r] = rank_failed[r] ? -1 : next++;
+  *n_live = next;
+}
+
 static int check_config(const revive_config& c) {
   const int64_t P = static_cast<int64_t>(c.n_ranks) * c.slots_per_rank;
   if (c.T_max < 0 || c.H <= 0 || c.E <= 0 || c.k <= 0 || c.I <= 0 || c.I_shared < 0 || c.n_ranks <= 0 ||
@@ -195,7 +205,9 @@ int revive_create(const revive_config* cfg, revive_ctx** out) {
   m.off_count = 0;
   m.off_table = align_up(m.off_count + sizeof(int32_t) * c.E, 16);
   m.off_alive = align_up(m.off_table + sizeof(int32_t) * c.E * c.max_replicas, 16);
-  m.bytes = align_up(m.off_alive + static_cast<size_t>(P), 16);
+  m.off_lrank = align_up(m.off_alive + static_cast<size_t>(P), 16);
+  m.off_nlive = align_up(m.off_lrank + sizeof(int32_t) * c.n_ranks, 16);
+  m.bytes = align_up(m.off_nlive + 4 * sizeof(int32_t), 16);
 
   const int64_t N_max = static_cast<int64_t>(c.T_max) * c.k;
   const int tile_m = c.dtype == REVIVE_DTYPE_BF16 ? kTileM_bf16 : kTileM_f32;
@@ -305,6 +317,8 @@ int revive_update_map_experts(revive_ctx* ctx, const uint8_t* rank_failed, const
                         reinterpret_cast<int32_t*>(blob.data() + ctx->map.off_count),
                         reinterpret_cast<int32_t*>(blob.data() + ctx->map.off_table), blob.data() + ctx->map.off_alive, &st);
   if (rc != REVIVE_OK) return rc;
+  compacted_ranks(rank_failed, c.n_ranks, reinterpret_cast<int32_t*>(blob.data() + ctx->map.off_lrank),
+                  reinterpret_cast<int32_t*>(blob.data() + ctx->map.off_nlive));
 
   const int b = ctx->stage_next;
   if (ctx->stage_used[b]) REVIVE_HIP(ctx, hipEventSynchronize(ctx->stage_done[b]));  // previous copy from this buffer
@@ -327,6 +341,14 @@ int revive_get_map(const revive_ctx* ctx, int32_t* l2p_table, int32_t* l2p_count
   if (l2p_count) std::memcpy(l2p_count, ctx->host_blob.data() + ctx->map.off_count, sizeof(int32_t) * c.E);
   if (l2p_table) std::memcpy(l2p_table, ctx->host_blob.data() + ctx->map.off_table, sizeof(int32_t) * c.E * c.max_replicas);
   if (slot_alive) std::memcpy(slot_alive, ctx->host_blob.data() + ctx->map.off_alive, ctx->P);
+  return REVIVE_OK;
+}
+
+int revive_get_rank_map(const revive_ctx* ctx, int32_t* logical_rank, int32_t* n_live_ranks) {
+  if (!ctx) return fail(ctx, REVIVE_EINVAL, "revive_get_rank_map: null context");
+  if (!ctx->map_set) return fail(ctx, REVIVE_ESTATE, "revive_get_rank_map: no map has been built yet");
+  if (logical_rank) std::memcpy(logical_rank, ctx->host_blob.data() + ctx->map.off_lrank, sizeof(int32_t) * ctx->cfg.n_ranks);
+  if (n_live_ranks) std::memcpy(n_live_ranks, ctx->host_blob.data() + ctx->map.off_nlive, sizeof(int32_t));
   return REVIVE_OK;
 }
 
@@ -410,6 +432,13 @@ int revive_dispatch(revive_ctx* ctx, const void* x, const int32_t* topk_phys, in
   if (!slot_offsets) return fail(ctx, REVIVE_EINVAL, "revive_dispatch: null slot_offsets");
   if (T > 0 && (!x || !topk_phys || !x_perm || !dst_row || !src_of)) return fail(ctx, REVIVE_EINVAL, "revive_dispatch: null argument");
   return launch_dispatch(ctx, x, topk_phys, T, x_perm, slot_offsets, dst_row, src_of, static_cast<hipStream_t>(stream));
+}
+
+int revive_rank_offsets(revive_ctx* ctx, const int32_t* slot_offsets, int32_t* rank_offsets, revive_stream stream) {
+  if (!ctx) return fail(ctx, REVIVE_EINVAL, "revive_rank_offsets: null context");
+  if (!ctx->map_set) return fail(ctx, REVIVE_ESTATE, "revive_rank_offsets: call revive_update_map first");
+  if (!slot_offsets || !rank_offsets) return fail(ctx, REVIVE_EINVAL, "revive_rank_offsets: null argument");
+  return launch_rank_offsets(ctx, slot_offsets, rank_offsets, static_cast<hipStream_t>(stream));
 }
 
 int revive_dispatch_static(revive_ctx* ctx, const void* x, const int32_t* topk_phys, int32_t T, void* x_perm,

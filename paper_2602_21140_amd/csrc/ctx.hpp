@@ -63,6 +63,8 @@ struct MapLayout {
   size_t off_count;   // int32 [E]
   size_t off_table;   // int32 [E * max_replicas]
   size_t off_alive;   // uint8 [P] (padded to 4)
+  size_t off_lrank;   // int32 [R]: compacted logical rank of each simulated rank, -1 = failed
+  size_t off_nlive;   // int32 [4]: [0] = number of live ranks
   size_t bytes;
 };
 
@@ -123,6 +125,8 @@ struct revive_ctx {
   const int32_t* d_l2p_count() const { return reinterpret_cast<const int32_t*>(d_map + map.off_count); }
   const int32_t* d_l2p_table() const { return reinterpret_cast<const int32_t*>(d_map + map.off_table); }
   const uint8_t* d_slot_alive() const { return d_map + map.off_alive; }
+  const int32_t* d_logical_rank() const { return reinterpret_cast<const int32_t*>(d_map + map.off_lrank); }
+  const int32_t* d_n_live_ranks() const { return reinterpret_cast<const int32_t*>(d_map + map.off_nlive); }
 };
 
 namespace revive {
@@ -161,6 +165,7 @@ int launch_dispatch(revive_ctx*, const void* x, const int32_t* topk_phys, int T,
 int init_static_dispatch_scratch(revive_ctx*);  // looks up this device's copy of the static scratch, once per device
 int launch_dispatch_static(revive_ctx*, const void* x, const int32_t* topk_phys, int T, void* x_perm,
                            int32_t* slot_offsets, int32_t* dst_row, int32_t* src_of, hipStream_t);
+int launch_rank_offsets(revive_ctx*, const int32_t* slot_offsets, int32_t* rank_offsets, hipStream_t);
 int launch_expert_ffn(revive_ctx*, const void* x_perm, const int32_t* slot_offsets, const void* const* w_gate_up,
                       const void* const* w_down, void* y_perm, const void* x, const void* w_sh_gate_up,
                       const void* w_sh_down, void* y_shared, int T, hipStream_t);

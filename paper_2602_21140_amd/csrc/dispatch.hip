@@ -168,7 +168,32 @@ __global__ __launch_bounds__(kThreads) void dispatch_permute_kernel(const uint4*
   }
 }
 
+// Compacted rank segments (Sec. 3.5): after the failed ranks have left the communication domain the
+// survivors are renumbered 0 .. n_live-1 in their old order; segment l of the permuted buffer is the
+// rows of the rank that now holds logical rank l.  Failed ranks received no rows, so the compacted
+// segments tile [0, N) without gaps; entries n_live .. R all hold N.
+__global__ __launch_bounds__(256) void rank_offsets_kernel(const int32_t* __restrict__ slot_offsets,
+                                                           const int32_t* __restrict__ logical_rank,
+                                                           const int32_t* __restrict__ n_live_ranks, int R, int S,
+                                                           int32_t* __restrict__ rank_offsets) {
+  const int n_live = n_live_ranks[0];
+  const int total = slot_offsets[R * S];
+  for (int r = threadIdx.x; r <= R; r += 256) {
+    if (r < R) {
+      const int l = logical_rank[r];
+      if (l >= 0) rank_offsets[l] = slot_offsets[r * S];
+    }
+    if (r >= n_live) rank_offsets[r] = total;
+  }
+}
+
 }  // namespace
+
+int launch_rank_offsets(revive_ctx* ctx, const int32_t* slot_offsets, int32_t* rank_offsets, hipStream_t stream) {
+  hipLaunchKernelGGL(rank_offsets_kernel, dim3(1), dim3(256), 0, stream, slot_offsets, ctx->d_logical_rank(), ctx->d_n_live_ranks(),
+                     ctx->cfg.n_ranks, ctx->cfg.slots_per_rank, rank_offsets);
+  return check_hip(ctx, hipGetLastError(), "rank_offsets launch");
+}
 
 // The two dispatch kernels with their scratch (chunk histograms, ticket) at the given addresses.
 static int run_dispatch(revive_ctx* ctx, const void* x, const int32_t* topk_phys, int T, void* x_perm, int32_t* slot_offsets,

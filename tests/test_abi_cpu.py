@@ -145,3 +145,22 @@ def test_compact_ranks_matches_oracle():
         assert pk.compact_ranks(ranks, f, sw).tolist() == orc.compact_ranks(ranks, f, sw)
     with pytest.raises(pk.ReviveError):
         pk.compact_ranks([0, -1, 1], 1)
+
+
+def test_library_sufficiency_test_over_every_live_mask():
+    """The library's refusal (REVIVE_EINSUFFICIENT_EXPERTS) against the oracle's sufficiency test,
+    itself pinned by brute force over rankings, for every set of live experts of an 8-expert layer in
+    4 groups and every (k, topk_group)."""
+    pk = _pk()
+    base = synth.get_config("c1")
+    p2l = np.arange(8, dtype=np.int32)
+    none = np.zeros(8, np.uint8)
+    for topk_group in (1, 2, 3, 4):
+        for k in range(1, 2 * topk_group + 1):
+            cfg = synth.scaled(base, E=8, k=k, n_group=4, topk_group=topk_group, n_ranks=8, slots_per_rank=1,
+                               max_replicas=1, score_fn="sigmoid")
+            for bits in range(1 << 8):
+                ef = np.array([1 - ((bits >> e) & 1) for e in range(8)], dtype=np.uint8)
+                rc, _t, count, _a, _s = pk.build_map_host(cfg, p2l, none, expert_failed=ef)
+                assert rc in (0, -4)
+                assert (rc == 0) == orc.enough_live_experts(count, k, 4, topk_group), (bits, k, topk_group)

@@ -1,0 +1,73 @@
+"""Device-resident rank compaction (Sec. 3.5): after a failure the surviving ranks are renumbered
+and the failed ranks' segments vanish from the layout of the dispatched buffer.  The table lives
+next to the expert map, so a map update changes it under the same captured graph."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import revive_oracle as orc
+from harness import GpuLayer
+
+pytestmark = pytest.mark.gpu
+
+
+def _expected_ranks(R, failed, order_rng):
+    ranks = list(range(R))
+    for f in order_rng.permutation(sorted(failed)):      # one failure at a time, in a random order
+        ranks = orc.compact_ranks(ranks, int(f))
+    return ranks
+
+
+@pytest.mark.parametrize("name", ["c3s", "c5s", "max"])
+def test_rank_table_and_compacted_segments_under_one_graph(name):
+    from test_gpu_parity import SMALL
+    cfg = SMALL[name]
+    g = GpuLayer(cfg, failed=[], with_weights=False)
+    try:
+        R, S = cfg.n_ranks, cfg.slots_per_rank
+        L, b = g.layer, g.buf
+        rank_offs = L.empty(R + 1, dtype=torch.int32)
+        logits = synth.draw_logits(cfg, g.device)
+        b["logits"].copy_(logits)
+        torch.cuda.synchronize()
+        stream = torch.cuda.Stream()
+        rng = np.random.default_rng(21)
+
+        def step(s):
+            L.route(None, None, cfg.T, logits=b["logits"], logits_given=True,
+                    out=(b["topk_logical"], b["topk_weight"], b["topk_phys"]), stream=s)
+            L.dispatch(g.x, b["topk_phys"], cfg.T, out=(b["x_perm"], b["slot_offsets"], b["dst_row"], b["src_of"]), stream=s)
+            L.rank_offsets(b["slot_offsets"], out=rank_offs, stream=s)
+
+        with torch.cuda.stream(stream):
+            step(stream)
+            stream.synchronize()
+            L.graph_begin(stream)
+            step(stream)
+            graph = L.graph_end(stream)
+            exec_id = L.graph_exec_id(graph)
+            sets = [[], list(cfg.failed_ranks), [0], [R - 1], [0, R - 1], list(range(1, R, 2))[: R // 3], []]
+            for failed in sets:
+                try:
+                    g.set_failed(failed, stream=stream)
+                except Exception:
+                    continue                                  # too few experts left for this set: skip it
+                rank_offs.fill_(-7)
+                L.graph_launch(graph, stream)
+                stream.synchronize()
+                want = _expected_ranks(R, failed, rng)
+                got, n_live = L.get_rank_map()
+                assert got.tolist() == want and n_live == R - len(failed)
+                m = g.oracle_map()
+                s = orc.scores(logits.double().cpu().numpy(), cfg.score_fn)
+                top = orc.select_topk(orc.masked_selection_scores(s, m.l2p_count), cfg.k, cfg.n_group, cfg.topk_group)
+                offs, _, _ = orc.dispatch_indices(orc.remap(top, m), cfg.P)
+                assert np.array_equal(b["slot_offsets"].cpu().numpy(), offs)
+                ref = orc.compacted_rank_offsets(offs, want, S)
+                assert rank_offs.cpu().numpy().tolist() == ref, failed
+                # the compacted segments tile [0, N) in order: no hole where a failed rank used to be
+                assert ref[0] == 0 and ref[n_live] == cfg.T * cfg.k and all(x <= y for x, y in zip(ref, ref[1:]))
+            assert L.graph_exec_id(graph) == exec_id
+    finally:
+        g.close()

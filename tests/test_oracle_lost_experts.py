@@ -108,3 +108,33 @@ def test_rank_compaction_follows_the_papers_description():
         assert sorted(others, key=lambda d: ranks[d]) == sorted(others, key=lambda d: new[d])   # order kept
         if sw >= 0 and ranks[sw] < 0:
             assert new[sw] == ranks[f] and all(new[d] == ranks[d] for d in others)
+
+
+def test_compacted_rank_offsets_by_hand():
+    """Sec. 3.5: after compaction the failed ranks are no part of the layout.  Four devices with
+    two slots each, rows per slot 3,1 | 0,0 | 2,2 | 5,0; device 1 failed (it holds no rows)."""
+    offs = [0, 3, 4, 4, 4, 6, 8, 13, 13]
+    assert orc.compacted_rank_offsets(offs, [0, -1, 1, 2], 2) == [0, 4, 8, 13, 13]
+    # nobody failed: the plain rank boundaries
+    offs_all = [0, 3, 4, 5, 5, 7, 9, 14, 14]
+    assert orc.compacted_rank_offsets(offs_all, [0, 1, 2, 3], 2) == [0, 4, 5, 9, 14]
+    # a switched-in device that took logical rank 1 while physically sitting last
+    assert orc.compacted_rank_offsets(offs, [0, -1, 2, 1], 2) == [0, 8, 4, 13, 13]
+    with pytest.raises(AssertionError):
+        orc.compacted_rank_offsets(offs_all, [0, -1, 1, 2], 2)      # a device outside the domain holding rows
+
+
+def test_removing_failed_ranks_one_at_a_time_gives_the_same_table_in_any_order():
+    r = np.random.default_rng(9)
+    for _ in range(30):
+        R = int(r.integers(2, 20))
+        failed = [int(d) for d in r.choice(R, size=int(r.integers(0, R)), replace=False)]
+        ranks = list(range(R))
+        for f in failed:
+            ranks = orc.compact_ranks(ranks, f)
+        again = list(range(R))
+        for f in sorted(failed):
+            again = orc.compact_ranks(again, f)
+        assert ranks == again
+        live = [d for d in range(R) if d not in failed]
+        assert [ranks[d] for d in live] == list(range(len(live))) and all(ranks[f] == -1 for f in failed)

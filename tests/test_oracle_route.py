@@ -233,3 +233,62 @@ def test_hand_worked_gating_examples(case):
     top = orc.select_topk(orc.masked_selection_scores(s, count), k, n_group, topk_group)
     assert top[0].tolist() == ids
     assert np.allclose(orc.gate_weights(s, top)[0], weights, rtol=0, atol=1e-12)
+
+
+def test_enough_live_experts_against_every_possible_ranking():
+    """The sufficiency test of the map update is a worst case over all logits.  Brute force on 6
+    experts in 3 groups: for every set of live experts and every (k, topk_group), a token can always
+    be given k live experts exactly when no ranking of the experts' scores makes the selection run
+    out of live experts (select_topk asserts when it does).  Scores 1..6 in every order reach every
+    ranking of experts and of group sums that matters here."""
+    import itertools
+    E, n_group = 6, 3
+    perms = np.array(list(itertools.permutations(range(1, E + 1))), dtype=np.float64)
+    checked = refused = 0
+    for bits in range(1, 1 << E):
+        count = np.array([(bits >> e) & 1 for e in range(E)], dtype=np.int32)
+        sel = orc.masked_selection_scores(perms, count)
+        for topk_group in (1, 2, 3):
+            for k in (1, 2, 3, 4):
+                if k > (E // n_group) * topk_group:
+                    continue                    # more experts than the kept groups hold at all: not a valid layer
+                try:
+                    top = orc.select_topk(sel, k, n_group, topk_group)
+                    always = bool((count[top] > 0).all())
+                except AssertionError:
+                    always = False
+                assert orc.enough_live_experts(count, k, n_group, topk_group) == always, (bits, k, topk_group)
+                checked += 1
+                refused += not always
+    assert checked > 500 and 0 < refused < checked
+    # ungrouped: plain count of live experts, against the same brute force
+    for bits in range(1, 1 << E):
+        count = np.array([(bits >> e) & 1 for e in range(E)], dtype=np.int32)
+        sel = orc.masked_selection_scores(perms[:120], count)
+        for k in (1, 2, 3, 6):
+            try:
+                orc.select_topk(sel, k)
+                always = True
+            except AssertionError:
+                always = False
+            assert orc.enough_live_experts(count, k, 1, 1) == always
+
+
+def test_enough_live_experts_by_keepable_group_subsets():
+    """8 experts in 4 groups, every live mask and every (k, topk_group): enumerate every set of
+    groups the gate can end up keeping (any topk_group live groups; when fewer groups are live, all
+    of them padded with dead ones) and ask whether each holds k live experts."""
+    import itertools
+    E, n_group, gsz = 8, 4, 2
+    for bits in range(1 << E):
+        live = np.array([(bits >> e) & 1 for e in range(E)], dtype=np.int32)
+        per_group = live.reshape(n_group, gsz).sum(axis=1)
+        live_groups = [g for g in range(n_group) if per_group[g] > 0]
+        for topk_group in range(1, n_group + 1):
+            if len(live_groups) >= topk_group:
+                keepable = list(itertools.combinations(live_groups, topk_group))
+            else:
+                keepable = [tuple(live_groups)]          # the dead groups that pad the set add no expert
+            worst = min(sum(per_group[g] for g in G) for G in keepable)
+            for k in range(1, gsz * topk_group + 1):
+                assert orc.enough_live_experts(live, k, n_group, topk_group) == (worst >= k), (bits, k, topk_group)
