@@ -122,10 +122,26 @@ def cpu_baseline(cfg, g, sample_tokens):
                       f"{cfg.E} experts' weights, combine), {dt:.2f} s"}
 
 
-def check_against_oracle(cfg, g, n_tokens, n_out_tokens, seed):
-    """Is the step that has just run the layer under the map now in force?  Compares, for sampled tokens, the
-    chosen experts and slots with the oracle's selection and remap under that map (on the step's own logits),
-    and for a few of them the complete output row with the oracle's fp64 layer."""
+def snapshot_step(cfg, g, n_tokens, n_out_tokens, seed):
+    """Host copies of what the step that has just run produced for a seeded sample of tokens (a few
+    device gathers; no arithmetic), to be judged later by check_against_oracle."""
+    import numpy as np
+    import torch
+    rng = np.random.default_rng(seed)
+    toks = np.sort(rng.choice(cfg.T, size=min(n_tokens, cfg.T), replace=False))
+    idx = torch.from_numpy(toks).to(g.device)
+    b = g.buf
+    sub = idx[:n_out_tokens]
+    return {"toks": toks, "failed": g.failed.copy(),
+            "logits": b["logits"][idx].to(torch.float64).cpu().numpy(),
+            "topk_logical": b["topk_logical"][idx].cpu().numpy(), "topk_phys": b["topk_phys"][idx].cpu().numpy(),
+            "x": g.x[sub].to(torch.float64).cpu().numpy(), "out": b["out"][sub].to(torch.float64).cpu().numpy()}
+
+
+def check_against_oracle(cfg, g, snap):
+    """Was the snapshotted step the layer under the map then in force?  Compares, for the sampled tokens,
+    the chosen experts and slots with the oracle's selection and remap under that map (on the step's own
+    logits), and for the first few of them the complete output row with the oracle's fp64 layer."""
     import numpy as np
     import torch
     import synth
@@ -134,30 +150,26 @@ def check_against_oracle(cfg, g, n_tokens, n_out_tokens, seed):
     def f64(t):
         return t.detach().to(torch.float64).cpu().numpy()
 
-    rng = np.random.default_rng(seed)
-    toks = np.sort(rng.choice(cfg.T, size=min(n_tokens, cfg.T), replace=False))
-    idx = torch.from_numpy(toks).to(g.device)
-    b = g.buf
-    m = orc.build_map(g.p2l, g.failed, cfg.slots_per_rank, cfg.E, cfg.max_replicas)
-    s = orc.scores(f64(b["logits"][idx]), cfg.score_fn)
+    toks = snap["toks"]
+    m = orc.build_map(g.p2l, snap["failed"], cfg.slots_per_rank, cfg.E, cfg.max_replicas)
+    s = orc.scores(snap["logits"], cfg.score_fn)
     ref_l = orc.select_topk(orc.masked_selection_scores(s, m.l2p_count), cfg.k, cfg.n_group, cfg.topk_group)
     ref_p = np.stack([[m.l2p_table[e, t % m.l2p_count[e]] for e in row] for t, row in zip(toks, ref_l)])
-    ok = bool(np.array_equal(b["topk_logical"][idx].cpu().numpy(), ref_l) and
-              np.array_equal(b["topk_phys"][idx].cpu().numpy(), ref_p))
+    ok = bool(np.array_equal(snap["topk_logical"], ref_l) and np.array_equal(snap["topk_phys"], ref_p))
     err = None
-    if ok and n_out_tokens > 0:
-        sub = np.arange(min(n_out_tokens, len(toks)))
-        w = orc.gate_weights(s[sub], ref_l[sub])
-        xs = f64(g.x[idx[sub]])
-        ref = np.zeros((len(sub), cfg.H))
-        for a in sub:
+    n_out = snap["out"].shape[0]
+    if ok and n_out > 0:
+        w = orc.gate_weights(s[:n_out], ref_l[:n_out])
+        xs = snap["x"]
+        ref = np.zeros((n_out, cfg.H))
+        for a in range(n_out):
             for j in range(cfg.k):
                 we = {n: f64(t) for n, t in synth.draw_expert(cfg, int(ref_l[a, j]), g.device).items()}
                 ref[a] += w[a, j] * orc.swiglu_ffn(xs[a:a + 1], we["gate"], we["up"], we["down"])[0]
         sh = synth.draw_shared(cfg, g.device)
         if sh is not None:
             ref += orc.swiglu_ffn(xs, f64(sh["gate"]), f64(sh["up"]), f64(sh["down"]))
-        err = float(np.abs(f64(b["out"][idx[sub]]) - ref).max() / np.abs(ref).max())
+        err = float(np.abs(snap["out"] - ref).max() / np.abs(ref).max())
         ok = ok and err < (1e-2 if cfg.dtype == "bf16" else 1e-4)
     return ok, err
 
@@ -248,9 +260,11 @@ def main():
         other = [r for r in range(cfg.n_ranks) if r not in cfg.failed_ranks]
         new_failed = list(cfg.failed_ranks[:-1]) + [other[len(other) // 2]] if cfg.failed_ranks else [other[0]]
         try_failed = new_failed if args.workload != "c5" else []
-        remap = []
+        remap, snaps = [], []
         for trial in range(5):
             target = try_failed if trial % 2 == 0 else list(cfg.failed_ranks)
+            for _ in range(2):          # steady steps under the map still in force, so that the flip meets a busy GPU
+                g.replay(stream)
             stream.synchronize()
             t0 = time.perf_counter()
             g.set_failed(target, stream=stream)
@@ -261,16 +275,16 @@ def main():
             phys = g.buf["topk_phys"]
             dead = torch.from_numpy(np.repeat(g.failed, cfg.slots_per_rank)).to(phys.device)
             ok = not bool(dead[phys.long()].any().item())
-            # outside the timed region: that first step against the oracle under the new map (every trial the
-            # routing of sampled tokens, the first two trials also complete output rows)
-            match, err = (None, None)
+            remap.append(((t1 - t0) * 1e3, (t2 - t0) * 1e3, ok))
+            # what that first step produced for sampled tokens, judged against the oracle once the timing is over
+            # (every trial the routing, the first two trials also complete output rows)
             if not args.no_cpu_baseline:
-                match, err = check_against_oracle(cfg, g, 256, 2 if trial < 2 else 0, seed=100 + trial)
-            remap.append(((t1 - t0) * 1e3, (t2 - t0) * 1e3, ok, match, err))
+                snaps.append(snapshot_step(cfg, g, 256, 2 if trial < 2 else 0, seed=100 + trial))
         g.set_failed(cfg.failed_ranks, stream=stream)
         g.replay(stream)   # leave the buffers as the workload's own failure set produces them
         stream.synchronize()
         same_exec = L.graph_exec_id(g.graph) == exec_id
+    remap_checks = [check_against_oracle(cfg, g, sn) for sn in snaps]
 
     micro = None
     if args.microbatches > 1:
@@ -372,8 +386,8 @@ def main():
         "stages": stages,
         "remap": {"update_map_host_ms": host_ms, "update_to_first_step_done_ms": first_ms,
                   "minus_steady_step_ms": first_ms - ms_per_step, "routes_avoid_failed_ranks": all(r[2] for r in remap),
-                  "first_step_matches_oracle_under_new_map": (None if args.no_cpu_baseline else all(r[3] for r in remap)),
-                  "first_step_out_rel_err": [r[4] for r in remap if r[4] is not None],
+                  "first_step_matches_oracle_under_new_map": (None if args.no_cpu_baseline else all(c[0] for c in remap_checks)),
+                  "first_step_out_rel_err": [c[1] for c in remap_checks if c[1] is not None],
                   "same_graph_exec": same_exec},
     }
     if micro is not None:
