@@ -209,7 +209,7 @@ def main():
     import numpy as np
     import torch
     import synth
-    from paper_2602_21140_amd.layer import ResidentLayer
+    from synth.resident import ResidentLayer
 
     cfg = synth.get_config(args.workload)
     if args.skew != 0.0:
@@ -288,7 +288,7 @@ def main():
 
     micro = None
     if args.microbatches > 1:
-        from paper_2602_21140_amd.layer import MicrobatchPipeline
+        from synth.resident import MicrobatchPipeline
         pipe = MicrobatchPipeline(g, args.microbatches)
         with torch.cuda.stream(stream):
             pipe.forward(stream)

@@ -7,7 +7,7 @@ experts, the share of (token, choice) pairs that move, and the share of the unfa
 combine weight that sat on failed experts.  The paper's accuracy numbers need DeepSeek V3 weights
 and benchmark datasets and are not reproduced; this only exercises the masks through the library.
 
-Usage: python -m paper_2602_21140_amd.lost_expert_study [--workload c3]
+Usage: python -m synth.lost_expert_study [--workload c3]
 """
 from __future__ import annotations
 
@@ -19,8 +19,8 @@ import torch
 
 import synth
 
-from .binding import mask_every_nth, mask_most_activated
-from .layer import ResidentLayer
+from paper_2602_21140_amd.binding import mask_every_nth, mask_most_activated
+from synth.resident import ResidentLayer
 
 
 def main():

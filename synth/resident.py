@@ -1,6 +1,7 @@
-"""A layer resident in HBM: seeded inputs, per-slot packed weights, preallocated outputs.
+"""A seeded workload resident in HBM: inputs, per-slot packed weights, preallocated outputs.
 
-Plumbing around the binding for the tests, the smoke check and the benchmark: it draws the
+This module is the GPU side of `synth` (the generators in `gen.py` and `configs.py` serve the CPU
+oracle's tests as well and never import it).  Plumbing around the binding for the tests, the smoke check and the benchmark: it draws the
 synthetic workload on the device, packs the weights into the library's layouts, owns every
 buffer the four data-path calls write, and can record those calls into one graph.  All compute
 happens inside the library calls.
@@ -13,8 +14,7 @@ import numpy as np
 import torch
 
 import synth
-
-from .binding import ReviveLayer, pack_expert, pack_router
+from paper_2602_21140_amd.binding import ReviveLayer, pack_expert, pack_router
 
 
 class ResidentLayer:

@@ -10,7 +10,7 @@ import torch
 
 import synth
 from oracle import revive_oracle as orc
-from paper_2602_21140_amd.layer import ResidentLayer
+from synth.resident import ResidentLayer
 
 TOL = {"fp32": 1e-4, "bf16": 1e-2}
 

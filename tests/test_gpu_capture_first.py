@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 PROGRAM = r"""
 import torch
 import synth
-from paper_2602_21140_amd.layer import ResidentLayer
+from synth.resident import ResidentLayer
 
 for name, kw in (("c3", dict(T=900, H=512, I=256, I_shared=256)), ("c1", dict())):
     cfg = synth.scaled(synth.get_config(name), **kw)

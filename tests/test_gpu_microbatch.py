@@ -8,7 +8,7 @@ import torch
 import synth
 from oracle import revive_oracle as orc
 from harness import GpuLayer, TOL, f64, rel_err
-from paper_2602_21140_amd.layer import MicrobatchPipeline
+from synth.resident import MicrobatchPipeline
 
 pytestmark = pytest.mark.gpu
 

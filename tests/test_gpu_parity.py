@@ -434,3 +434,35 @@ def test_random_sequence_of_map_updates_under_one_graph():
             assert accepted > 20 and refused > 0
     finally:
         g.close()
+
+
+@pytest.mark.parametrize("name", ["c2m", "c4s"])
+def test_a_masked_expert_with_a_towering_logit_leaves_the_weights_finite(name):
+    """Sec. 3.4 "Missing experts": a masked expert takes no part in the selection, whatever its logit.
+    Here every lost expert's logit towers a thousand above all live ones (reachable through given
+    logits): the chosen experts and their weights must be those of the live experts alone."""
+    cfg = SMALL[name]
+    g = GpuLayer(cfg, with_weights=False)
+    try:
+        m = g.oracle_map()
+        lost = np.nonzero(m.l2p_count == 0)[0]
+        assert lost.size > 0
+        logits = synth.draw_logits(cfg, g.device)
+        logits[:, torch.from_numpy(lost).to(g.device)] += 1000.0
+        _, top_l, top_w, top_p = g.layer.route(None, None, cfg.T, logits=logits, logits_given=True)
+        lg = f64(logits)
+        live = np.nonzero(m.l2p_count > 0)[0]
+        if cfg.score_fn == "softmax":      # the oracle's softmax over all logits underflows to 0/0 here: restrict it to the live ones,
+            s = np.zeros_like(lg)          # which gives the same selection and the same renormalised weights
+            s[:, live] = orc.scores(lg[:, live], "softmax")
+        else:
+            s = orc.scores(lg, cfg.score_fn)
+        ref_l = orc.select_topk(orc.masked_selection_scores(s, m.l2p_count), cfg.k, cfg.n_group, cfg.topk_group)
+        assert np.array_equal(_i(top_l), ref_l)
+        w = f64(top_w)
+        assert np.isfinite(w).all()
+        assert np.abs(w - orc.gate_weights(s, ref_l)).max() < 2e-7
+        assert np.abs(w.sum(axis=1) - 1.0).max() < 1e-6
+        assert np.array_equal(_i(top_p), orc.remap(ref_l, m))
+    finally:
+        g.close()
