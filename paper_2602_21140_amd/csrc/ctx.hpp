@@ -10,21 +10,15 @@
 #include <string>
 #include <vector>
 
+#include "map_host.hpp"
 #include "revive.h"
 
 namespace revive {
 
-constexpr int kMaxE = 512;
-constexpr int kMaxP = 1024;
-constexpr int kMaxK = 32;
 constexpr int kDispatchChunk = 1024;  // routed rows handled by one block of the count/place kernels
 constexpr int kStaticDispatchChunks = 64;  // chunks the statically allocated dispatch scratch holds (65536 routed rows)
 constexpr int kTimingPairs = 8192;    // event pairs kept before timing results are folded
 
-// Tile heights of the grouped GEMMs (rows of one slot handled by one workgroup).
-constexpr int kTileM_bf16 = 256;
-constexpr int kTileM_f32 = 64;
-constexpr int kMaxTilesPerSlot = 1 << 15;  // MTile::pad holds count and position in 16 bits each
 
 // One row-tile of a grouped GEMM.  All row-tiles of a group (physical slot) carry the same
 // record except for their position; tile_span() gives the rows of tile j.  The group's weight

@@ -72,17 +72,18 @@ __global__ __launch_bounds__(kMaxP) void dispatch_index_kernel(const int32_t* __
     block_hist[static_cast<int64_t>(blockIdx.x) * P + p] = total;
   }
 
-  // Publish this chunk's histogram device-wide, then take a ticket; only the workgroup holding the
-  // last ticket goes on (nobody waits for anybody).  The barrier orders the workgroup's stores
-  // before thread 0's release, and thread 0's acquire before the workgroup's later loads; one
-  // thread does the device-scope part because each such fence is a cache operation of its own.
-  // Every wavefront first waits until its own stores have been accepted by L2.
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  // Publish this chunk's histogram and ranks device-wide, then take a ticket; only the workgroup
+  // holding the last ticket goes on (nobody waits for anybody).  The usual release/acquire chain,
+  // every wavefront fencing for itself: stores, agent-scope release fence, workgroup barrier, one
+  // thread's atomic; and in the last workgroup: that atomic, workgroup barrier, agent-scope
+  // acquire fence in every wavefront, loads of what the other workgroups stored.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
   __syncthreads();
   if (threadIdx.x == 0)
-    last_flag = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1;
+    last_flag = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1;
   __syncthreads();
   if (!last_flag) return;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 
   // Column p of block_hist becomes exclusive running sums over the chunks (the rows of slot p that
   // earlier chunks hold); `run` ends as the column total.

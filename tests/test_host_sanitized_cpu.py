@@ -1,0 +1,128 @@
+"""The library's host-only code (map construction of the recovery step, sufficiency test, rank
+compaction, study masks) built with AddressSanitizer and UBSan by a plain C++ compiler and driven
+over random and edge cases: every result must equal the oracle's and the sanitizers must stay
+silent (any report aborts the driver with a non-zero status)."""
+import os
+import shutil
+import subprocess
+
+import numpy as np
+import pytest
+
+from oracle import revive_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2602_21140_amd", "csrc")
+
+
+@pytest.fixture(scope="module")
+def driver(tmp_path_factory):
+    cxx = shutil.which("g++")
+    if cxx is None:
+        pytest.skip("no g++")
+    exe = str(tmp_path_factory.mktemp("san") / "host_map_driver")
+    cmd = [cxx, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+           "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, os.path.join(CSRC, "map_host.cpp"),
+           os.path.join(ROOT, "tests", "host_map_driver.cpp"), "-o", exe]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    return exe
+
+
+def _run(exe, text):
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    env.pop("LD_PRELOAD", None)     # the sanitizer runtime must come first in the driver's own link order
+    r = subprocess.run([exe], input=text, capture_output=True, text=True, env=env)
+    assert r.returncode == 0, r.stderr[-2000:]
+    assert "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr, r.stderr[-2000:]
+    return [list(map(int, line.split())) for line in r.stdout.strip().splitlines()]
+
+
+def test_map_construction_under_sanitizers_matches_the_oracle(driver):
+    rng = np.random.default_rng(17)
+    cases, lines = [], []
+    for _ in range(300):
+        R = int(rng.integers(1, 9))
+        S = int(rng.integers(1, 6))
+        P = R * S
+        n_group = int(rng.choice([1, 1, 2, 4]))
+        E = n_group * int(rng.integers(1, 5))
+        topk_group = int(rng.integers(1, n_group + 1))
+        k = int(rng.integers(1, max(1, (E // n_group) * topk_group) + 1))
+        max_rep = int(rng.integers(1, 4))
+        pool = np.repeat(np.arange(E), max_rep)                      # at most max_rep copies of an expert, the rest empty
+        pool = np.concatenate([pool, np.full(max(0, P - pool.size) + 2, -1)])
+        p2l = rng.permutation(pool)[:P]
+        kind = rng.random()
+        if kind > 0.9:
+            p2l = rng.integers(-1, E, size=P)                         # unconstrained: often more copies than max_replicas
+        if kind < 0.1:
+            p2l[rng.integers(P)] = E + int(rng.integers(0, 3))        # expert id out of range
+        elif kind < 0.2:
+            p2l[rng.integers(P)] = -2 - int(rng.integers(0, 3))       # below -1
+        rf = (rng.random(R) < 0.3).astype(int)
+        if rng.random() < 0.05:
+            rf[rng.integers(R)] = int(rng.integers(2, 256))           # not a 0/1 byte
+        ef = (rng.random(E) < 0.2).astype(int) if rng.random() < 0.5 else None
+        cases.append((E, k, n_group, topk_group, R, S, max_rep, p2l, rf, ef))
+        lines.append(" ".join(map(str, ["map", E, k, n_group, topk_group, R, S, max_rep, *p2l, *rf,
+                                        *([1, *ef] if ef is not None else [0])])))
+    out = _run(driver, "\n".join(lines) + "\n")
+    assert len(out) == len(cases)
+    n_ok = n_few = n_bad = 0
+    for (E, k, n_group, topk_group, R, S, max_rep, p2l, rf, ef), got in zip(cases, out):
+        P = R * S
+        rc = got[0]
+        valid_ids = ((p2l >= -1) & (p2l < E)).all()
+        copies = np.bincount(p2l[(p2l >= 0) & (p2l < E)], minlength=E)
+        bad_bytes = (rf > 1).any()
+        if bad_bytes or not valid_ids or copies.max(initial=0) > max_rep:
+            assert rc == -1, (rc, p2l, rf)
+            n_bad += 1
+            continue
+        m = orc.build_map(p2l, rf, S, E, max_rep, expert_failed=ef)
+        enough = orc.enough_live_experts(m.l2p_count, k, n_group, topk_group)
+        assert rc == (0 if enough else -4)
+        n_ok += enough
+        n_few += not enough
+        stats, rest = got[1:5], got[5:]
+        assert stats == [m.n_live_slots, m.n_live_experts, m.n_lost_experts, m.n_degraded_experts]
+        assert rest[:E] == m.l2p_count.tolist()
+        assert rest[E:E + E * max_rep] == m.l2p_table.ravel().tolist()
+        assert rest[E + E * max_rep:E + E * max_rep + P] == m.slot_alive.tolist()
+        lrank = rest[E + E * max_rep + P:E + E * max_rep + P + R]
+        want = list(range(R))
+        for f in np.nonzero(rf)[0]:
+            want = orc.compact_ranks(want, int(f))
+        assert lrank == want and rest[-1] == R - int(rf.sum())
+    assert n_ok > 50 and n_few > 20 and n_bad > 20
+
+
+def test_rank_compaction_and_masks_under_sanitizers_match_the_oracle(driver):
+    rng = np.random.default_rng(18)
+    lines, want = [], []
+    for _ in range(200):
+        n = int(rng.integers(1, 12))
+        ranks = [-1] * n
+        members = [d for d in range(n) if rng.random() < 0.8]
+        for i, d in enumerate(rng.permutation(members)):
+            ranks[int(d)] = i
+        f, sw = int(rng.integers(-1, n + 1)), int(rng.integers(-2, n + 1))
+        lines.append(" ".join(map(str, ["ranks", n, f, sw, *ranks])))
+        ok = 0 <= f < n and sw < n and sw != f and ranks[f] >= 0
+        want.append([0, *orc.compact_ranks(ranks, f, sw if sw >= 0 else -1)] if ok else [-1, *ranks])
+    for E, n in ((8, 2), (10, 3), (1, 1), (7, 100), (5, 0), (0, 2)):
+        lines.append(f"nth {E} {n}")
+        want.append([0, *orc.every_nth_mask(E, n).tolist()] if E > 0 and n > 0 else None)
+    for _ in range(60):
+        E = int(rng.integers(1, 40))
+        counts = rng.integers(0, 4, size=E)
+        n_fail = int(rng.integers(-1, E + 2))
+        lines.append(" ".join(map(str, ["top", E, n_fail, *counts])))
+        want.append([0, *orc.most_activated_mask(counts, n_fail).tolist()] if 0 <= n_fail <= E else None)
+    out = _run(driver, "\n".join(lines) + "\n")
+    assert len(out) == len(want)
+    for got, w in zip(out, want):
+        if w is None:
+            assert got[0] == -1
+        else:
+            assert got == w
