@@ -242,6 +242,13 @@ int revive_route(revive_ctx* ctx, const void* x, const void* w_router, float* lo
                  int32_t logits_given, int32_t T, int32_t* topk_logical, float* topk_weight,
                  int32_t* topk_phys, revive_stream stream);
 
+/* Microbatches (Sec. 2.2): when x holds rows [first_token, first_token + T) of a
+ * larger batch, the replica rule of revive_route uses the token's index in the
+ * whole batch, (first_token + t) mod count[e], so that the microbatches choose
+ * the very slots the undivided batch would.  Host state of the context, read
+ * when revive_route is called (or recorded); default 0. */
+int revive_set_token_offset(revive_ctx* ctx, int64_t first_token);
+
 /* a6/a7 - Dispatch / A2E (Sec. 2.3): stable counting sort of the N = T*k routed
  * rows i = t*k + j by physical slot, and the row permutation.
  *   slot_offsets dev int32 [P+1]: exclusive prefix sum of rows per slot;

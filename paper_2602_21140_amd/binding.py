@@ -79,6 +79,7 @@ def lib() -> C.CDLL:
         "revive_build_map": (C.c_int, [P(Config), vp, vp, vp, vp, vp, P(MapStats)]),
         "revive_route": (C.c_int, [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]),
         "revive_dispatch": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp, vp]),
+        "revive_set_token_offset": (C.c_int, [vp, C.c_int64]),
         "revive_get_rank_map": (C.c_int, [vp, vp, vp]),
         "revive_rank_offsets": (C.c_int, [vp, vp, vp, vp]),
         "revive_dispatch_static": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp, vp]),
@@ -108,7 +109,7 @@ def lib() -> C.CDLL:
 EXPORTS = ["revive_create", "revive_destroy", "revive_workspace_bytes", "revive_bind_workspace",
            "revive_set_placement", "revive_update_map", "revive_update_map_experts", "revive_get_map", "revive_build_map",
            "revive_build_map_experts", "revive_compact_ranks", "revive_mask_every_nth", "revive_mask_most_activated", "revive_expert_counts",
-           "revive_get_rank_map", "revive_rank_offsets",
+           "revive_get_rank_map", "revive_rank_offsets", "revive_set_token_offset",
            "revive_route", "revive_dispatch", "revive_dispatch_static", "revive_expert_ffn", "revive_shared_ffn", "revive_combine",
            "revive_graph_begin", "revive_graph_end", "revive_graph_launch", "revive_graph_exec_id",
            "revive_graph_destroy", "revive_set_kernel_timing", "revive_kernel_time",
@@ -316,6 +317,10 @@ class ReviveLayer:
         alive = np.zeros(self.P, dtype=np.uint8)
         self._check(self.L.revive_get_map(self._ctx, table.ctypes.data, count.ctypes.data, alive.ctypes.data))
         return table, count, alive
+
+    def set_token_offset(self, first_token: int):
+        """revive_set_token_offset: x is rows [first_token, first_token + T) of a larger batch."""
+        self._check(self.L.revive_set_token_offset(self._ctx, int(first_token)))
 
     def get_rank_map(self):
         """(logical_rank int32[R], n_live_ranks) of the map in force (host copies)."""

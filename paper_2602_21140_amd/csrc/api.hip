@@ -222,6 +222,13 @@ int revive_update_map_experts(revive_ctx* ctx, const uint8_t* rank_failed, const
   return REVIVE_OK;
 }
 
+int revive_set_token_offset(revive_ctx* ctx, int64_t first_token) {
+  if (!ctx) return fail(ctx, REVIVE_EINVAL, "revive_set_token_offset: null context");
+  if (first_token < 0) return fail(ctx, REVIVE_EINVAL, "revive_set_token_offset: negative offset");
+  ctx->token_offset = first_token;
+  return REVIVE_OK;
+}
+
 int revive_get_map(const revive_ctx* ctx, int32_t* l2p_table, int32_t* l2p_count, uint8_t* slot_alive) {
   if (!ctx) return fail(ctx, REVIVE_EINVAL, "revive_get_map: null context");
   if (!ctx->map_set) return fail(ctx, REVIVE_ESTATE, "revive_get_map: no map has been built yet");

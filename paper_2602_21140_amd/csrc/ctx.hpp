@@ -89,6 +89,7 @@ struct revive_ctx {
   std::vector<int32_t> phys_to_logical;
   std::vector<int32_t> full_count;  // replicas per expert in the placement
   std::vector<uint8_t> host_blob;   // current tables, MapLayout order
+  int64_t token_offset = 0;  // index of row 0 of x within the whole batch (replica rule of a microbatch)
   bool placement_set = false;
   bool map_set = false;
 

@@ -22,6 +22,7 @@ struct RouteParams {
   float* topk_weight;
   int32_t* topk_phys;
   int T, E, k, max_replicas, score_fn, n_group, topk_group;
+  long long t_offset;  // index of token 0 within the whole batch
   float route_scale;
 };
 
@@ -140,8 +141,8 @@ __global__ __launch_bounds__(256) void route_topk_kernel(RouteParams p) {
     const int c = p.l2p_count[my_e];
     p.topk_logical[o] = my_e;
     p.topk_weight[o] = static_cast<float>(s / sum * static_cast<double>(p.route_scale));
-    // replica of this token: the (t mod count)-th surviving slot, ascending slot id
-    p.topk_phys[o] = c > 0 ? p.l2p_table[my_e * p.max_replicas + t % c] : -1;
+    // replica of this token: the (batch index of t mod count)-th surviving slot, ascending slot id
+    p.topk_phys[o] = c > 0 ? p.l2p_table[my_e * p.max_replicas + static_cast<int>((p.t_offset + t) % c)] : -1;
   }
 }
 
@@ -311,6 +312,7 @@ int launch_route_topk(revive_ctx* ctx, const float* logits, int T, int32_t* topk
   p.T = T; p.E = c.E; p.k = c.k; p.max_replicas = c.max_replicas;
   p.score_fn = c.score_fn; p.n_group = c.n_group; p.topk_group = c.topk_group;
   p.route_scale = c.route_scale;
+  p.t_offset = ctx->token_offset;
   KernelTimer timer(ctx, REVIVE_K_ROUTE_TOPK, stream);
   const dim3 grid(ceil_div(T, 4)), block(256);
   const int vals = ceil_div(c.E, 64);

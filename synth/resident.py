@@ -139,10 +139,9 @@ class MicrobatchPipeline:
 
     Every microbatch has its own context (map tables and workspace are per context) and its own
     intermediate buffers; weights, inputs and the output tensor are those of `base` (microbatch m
-    reads rows [m*T/n, (m+1)*T/n) of x and writes the same rows of out).  Token t of a microbatch
-    picks replica `t mod count` with t counted inside the microbatch, so topk_phys may differ from
-    the single-batch run where replicas exist; the layer output does not (replicas hold the same
-    weights and every output row is computed by the same arithmetic in the same order)."""
+    reads rows [m*T/n, (m+1)*T/n) of x and writes the same rows of out).  Every context is told
+    where its rows start in the whole batch, so a token picks the replica the undivided batch would
+    pick and topk_phys of the microbatches is the single batch's, row for row."""
 
     def __init__(self, base: ResidentLayer, n_micro: int = 2):
         cfg = base.cfg
@@ -157,6 +156,7 @@ class MicrobatchPipeline:
             L.set_placement(base.p2l)
             L.update_map(base.failed, expert_failed=base.expert_failed)
             L.set_expert_weights(base.gu, base.dn)
+            L.set_token_offset(m * Tm)          # replicas are chosen by the token's index in the whole batch
             rows = slice(m * Tm, (m + 1) * Tm)
             buf = dict(
                 x=base.x[rows], out=base.buf["out"][rows],
