@@ -351,9 +351,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   // Tile -> workgroup map.  Workgroup i runs on XCD i % 8; each XCD takes a contiguous eighth of
   // every problem's tiles (neighbouring tiles share activations / weights in that XCD's L2), and
   // works through the problem with the longer K first so that the cheap tiles fill the last round.
-  const int t0 = (a2.p0.tiles ? *a2.p0.tile_count : (a2.p0.M + BM - 1) / BM) * a2.p0.n_col_tiles;
-  const int t1 = a2.two ? (a2.p1.tiles ? *a2.p1.tile_count : (a2.p1.M + BM - 1) / BM) * a2.p1.n_col_tiles : 0;
-  const int px0 = (t0 + 7) >> 3, px1 = (t1 + 7) >> 3;
+  // A dense problem (no tile list) is split by whole row-tiles instead: XCD x owns n_m / 8 of them
+  // (the first n_m % 8 XCDs one more), so that the order below can walk its own block of the
+  // output; its workgroup budget per XCD is that of the XCDs with one more.
+  const int nm0 = a2.p0.tiles ? *a2.p0.tile_count : (a2.p0.M + BM - 1) / BM;
+  const int nm1 = a2.two ? (a2.p1.tiles ? *a2.p1.tile_count : (a2.p1.M + BM - 1) / BM) : 0;
+  const int t0 = nm0 * a2.p0.n_col_tiles, t1 = nm1 * a2.p1.n_col_tiles;
+  const int px0 = a2.p0.tiles ? (t0 + 7) >> 3 : ((nm0 + 7) >> 3) * a2.p0.n_col_tiles;
+  const int px1 = !a2.two ? 0 : a2.p1.tiles ? (t1 + 7) >> 3 : ((nm1 + 7) >> 3) * a2.p1.n_col_tiles;
   const int xcd = blockIdx.x & 7;
   int local = blockIdx.x >> 3;
   const bool p1_first = a2.two && a2.p1.K > a2.p0.K;
@@ -365,11 +370,28 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
     second = local >= px0;
     if (second) local -= px0;
   }
-  const int logical = xcd * (second ? px1 : px0) + local;
-  if (local >= (second ? px1 : px0) || logical >= (second ? t1 : t0)) return;
+  if (local >= (second ? px1 : px0)) return;
   const GemmArgs g = second ? a2.p1 : a2.p0;
-  int m_idx = logical / g.n_col_tiles;
-  int n_idx = logical - m_idx * g.n_col_tiles;
+  int m_idx, n_idx, logical = 0;
+  if (g.tiles) {
+    logical = xcd * (second ? px1 : px0) + local;
+    if (logical >= (second ? t1 : t0)) return;
+    m_idx = logical / g.n_col_tiles;
+    n_idx = logical - m_idx * g.n_col_tiles;
+  } else {
+    // The XCD's G row-tiles times all column tiles, column tiles taken in pairs and inside a pair
+    // the row-tile slower than the column: a row-tile's activations are needed again by the very
+    // next workgroup and a column tile's weights by the one after that, down the whole block,
+    // instead of the weights coming back only after a full row of column tiles.
+    const int nm = second ? nm1 : nm0;
+    const int G = (nm >> 3) + (xcd < (nm & 7));
+    if (local >= G * g.n_col_tiles) return;
+    const int blk = local / (2 * G), within = local - blk * 2 * G;
+    int j;
+    if (blk * 2 + 1 < g.n_col_tiles) { j = within >> 1; n_idx = blk * 2 + (within & 1); }
+    else { j = within; n_idx = blk * 2; }
+    m_idx = xcd * (nm >> 3) + min(xcd, nm & 7) + j;
+  }
 
   int row_begin, row_end;
   const unsigned char* Bbase;
@@ -805,8 +827,10 @@ int launch_gemm_bf16_dma(revive_ctx* ctx, const GemmArgs& p0, int max_m_tiles0, 
   a.p0 = p0;
   a.two = p1 != nullptr;
   if (p1) a.p1 = *p1;
-  const int64_t per_xcd = (static_cast<int64_t>(max_m_tiles0) * p0.n_col_tiles + 7) / 8 +
-                          (p1 ? (static_cast<int64_t>(max_m_tiles1) * p1->n_col_tiles + 7) / 8 : 0);
+  auto budget = [](const GemmArgs& p, int max_m_tiles) -> int64_t {  // workgroups per XCD, as the kernel splits the problem
+    return p.tiles ? (static_cast<int64_t>(max_m_tiles) * p.n_col_tiles + 7) / 8 : static_cast<int64_t>((max_m_tiles + 7) / 8) * p.n_col_tiles;
+  };
+  const int64_t per_xcd = budget(p0, max_m_tiles0) + (p1 ? budget(*p1, max_m_tiles1) : 0);
   if (per_xcd <= 0) return REVIVE_OK;
   const int grid = static_cast<int>(per_xcd * 8);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, stream, a);
