@@ -71,3 +71,39 @@ def test_rank_table_and_compacted_segments_under_one_graph(name):
             assert L.graph_exec_id(graph) == exec_id
     finally:
         g.close()
+
+
+def test_rank_calls_refuse_bad_arguments_and_handle_an_empty_batch():
+    import ctypes as C
+    from paper_2602_21140_amd.binding import ReviveError, ReviveLayer, lib
+    from test_gpu_parity import SMALL
+    cfg = SMALL["c2m"]
+    L = ReviveLayer(cfg)
+    try:
+        raw = lib()
+        R, P = cfg.n_ranks, cfg.n_ranks * cfg.slots_per_rank
+        offs = torch.zeros(P + 1, dtype=torch.int32, device=L.device)
+        out = torch.full((R + 1,), -7, dtype=torch.int32, device=L.device)
+        with pytest.raises(ReviveError) as e:                      # no map yet
+            L.rank_offsets(offs, out=out)
+        assert e.value.status == -3
+        with pytest.raises(ReviveError):
+            L.get_rank_map()
+        L.set_placement(synth.make_placement(cfg))
+        L.update_map(synth.failed_mask(cfg))
+        assert raw.revive_rank_offsets(L._ctx, None, out.data_ptr(), None) == -1
+        assert raw.revive_rank_offsets(L._ctx, offs.data_ptr(), None, None) == -1
+        assert raw.revive_set_token_offset(L._ctx, -1) == -1
+        assert raw.revive_set_token_offset(None, 0) == -1
+        # an empty batch: dispatch writes all-zero offsets, every compacted segment is empty
+        x = synth.draw_x(cfg, L.device)
+        phys = torch.zeros(0, cfg.k, dtype=torch.int32, device=L.device)
+        _xp, offs0, _d, _s = L.dispatch(x, phys, 0)
+        L.rank_offsets(offs0, out=out)
+        torch.cuda.synchronize()
+        assert out.cpu().numpy().tolist() == [0] * (R + 1)
+        lr, n_live = L.get_rank_map()
+        failed = synth.failed_mask(cfg)
+        assert n_live == R - int(failed.sum()) and all((lr[r] == -1) == bool(failed[r]) for r in range(R))
+    finally:
+        L.close()
