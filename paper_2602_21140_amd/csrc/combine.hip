@@ -19,6 +19,18 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+// Every routed row is read exactly once and every output word written once: both bypass the caches' retention
+// (non-temporal), which leaves the caches to the kernels before and after.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+__device__ __forceinline__ uint4 load_once(const uint4* p) {
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_once(uint4* p, uint4 o) {
+  const u32x4 v = {o.x, o.y, o.z, o.w};
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
+}
+
 // One workgroup per token, 16-byte words (8 bf16 or 4 fp32 per thread and step).
 template <bool BF16>
 __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ y_perm, const int32_t* __restrict__ dst_row,
@@ -44,7 +56,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
       for (int u = 0; u < 8; ++u) {
         const int r = j0 + u < k ? rows[j0 + u] : -1;
         on[u] = r >= 0;
-        v[u] = on[u] ? y_perm[static_cast<int64_t>(r) * row_words + c] : make_uint4(0, 0, 0, 0);
+        v[u] = on[u] ? load_once(y_perm + static_cast<int64_t>(r) * row_words + c) : make_uint4(0, 0, 0, 0);
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
@@ -81,7 +93,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
       o.x = __float_as_uint(acc[0]); o.y = __float_as_uint(acc[1]);
       o.z = __float_as_uint(acc[2]); o.w = __float_as_uint(acc[3]);
     }
-    out[static_cast<int64_t>(t) * row_words + c] = o;
+    store_once(out + static_cast<int64_t>(t) * row_words + c, o);
   }
 }
 
