@@ -20,6 +20,7 @@ __global__ __launch_bounds__(kMaxP) void ffn_tiles_kernel(const int32_t* __restr
                                                           const void* const* __restrict__ w_down,
                                                           MTile* __restrict__ tiles, int32_t* __restrict__ tile_count) {
   __shared__ int wave_sums[kMaxP / 64];
+  __shared__ int tile_base[kMaxP + 1];  // first row-tile of every slot (exclusive prefix sum), [P] = total
   const int p = threadIdx.x;
   int first = 0, end = 0;
   if (p < P) {
@@ -49,17 +50,29 @@ __global__ __launch_bounds__(kMaxP) void ffn_tiles_kernel(const int32_t* __restr
   }
   __syncthreads();
   const int base = wave_sums[wave] + incl - mine;
-  if (mine > 0) {  // only slots that received rows have their weight pointers read
-    MTile t;
-    t.group = p;
-    t.group_begin = first;
-    t.group_end = end;
-    t.w[0] = w_gate_up[p];
-    t.w[1] = w_down[p];
-    for (int i = 0; i < mine; ++i) {
-      t.pad = (mine << 16) | i;
-      tiles[base + i] = t;
+  if (p < P) tile_base[p] = base;
+  if (p == P - 1) tile_base[P] = base + mine;
+  __syncthreads();
+  // One record per row-tile, the records dealt to the threads in order (a slot that holds most of the
+  // rows, e.g. when every token picks the same experts, does not leave its thousands of records to one
+  // thread).  The slot of record i is the last one whose first record is <= i: a binary search over the
+  // prefix sums.  Only slots that received rows have their weight pointers read.
+  const int total = tile_base[P];
+  for (int i = p; i < total; i += kMaxP) {
+    int lo = 0, hi = P - 1;  // invariant: tile_base[lo] <= i, and the answer is in [lo, hi]
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (tile_base[mid] <= i) lo = mid; else hi = mid - 1;
     }
+    const int g = lo;  // among slots with equal base (empty ones) the last, which is the one that holds tiles
+    MTile t;
+    t.group = g;
+    t.group_begin = slot_offsets[g];
+    t.group_end = slot_offsets[g + 1];
+    t.pad = ((tile_base[g + 1] - tile_base[g]) << 16) | (i - tile_base[g]);
+    t.w[0] = w_gate_up[g];
+    t.w[1] = w_down[g];
+    tiles[i] = t;
   }
 }
 
