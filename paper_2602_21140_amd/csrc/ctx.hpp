@@ -144,7 +144,6 @@ int fold_timing(revive_ctx* ctx);
 hipError_t allow_dynamic_lds(const void* kernel, size_t lds);
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
-inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Upper bound on row-tiles of a grouped GEMM over N rows in at most `groups` non-empty groups.
 inline int max_tiles(int64_t n_rows, int groups, int tile_m) {

@@ -26,9 +26,6 @@ std::string& noctx_error() {
 // Ungrouped: at least k live experts.  Grouped: a group without live experts is kept only when
 // fewer than topk_group groups have one, so the worst kept set is the topk_group live groups
 // with the fewest live experts (or every live group when there are fewer than that).
-// Ungrouped: at least k live experts.  Grouped: a group without live experts is kept only when
-// fewer than topk_group groups have one, so the worst kept set is the topk_group live groups
-// with the fewest live experts (or every live group when there are fewer than that).
 bool enough_live(const revive_config& c, const int32_t* count) {
   if (c.n_group <= 1) {
     int live = 0;
