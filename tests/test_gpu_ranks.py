@@ -107,3 +107,40 @@ def test_rank_calls_refuse_bad_arguments_and_handle_an_empty_batch():
         assert n_live == R - int(failed.sum()) and all((lr[r] == -1) == bool(failed[r]) for r in range(R))
     finally:
         L.close()
+
+
+def test_hand_worked_rank_compaction_on_the_gpu():
+    """The device table and revive_rank_offsets against tests/golden/rank_compaction.txt (worked out by hand):
+    six ranks of two slots, ranks 1 and 4 failed, the fixture's rows per slot produced by routing rows there."""
+    import os
+    from paper_2602_21140_amd.binding import ReviveLayer
+    g = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "rank_compaction.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        key, *rest = line.split()
+        g[key] = [int(v) for v in rest]
+    R, S = 6, 2
+    offs = np.array(g["slot_offsets"])
+    rows = np.diff(offs)
+    N = int(offs[-1])
+    k = 2
+    cfg = synth.scaled(synth.get_config("c1"), T=N // k, E=12, k=k, n_ranks=R, slots_per_rank=S, max_replicas=1,
+                       failed_ranks=(1, 4), n_unprotected=-1)
+    L = ReviveLayer(cfg)
+    try:
+        L.set_placement(np.arange(R * S, dtype=np.int32))
+        L.update_map(np.array(g["rank_failed"], dtype=np.uint8))
+        lr, n_live = L.get_rank_map()
+        assert lr.tolist() == g["logical_rank"] and n_live == g["n_live"][0]
+        # routed rows that put exactly the fixture's number of rows on every slot, in a shuffled order
+        phys = np.repeat(np.arange(R * S), rows).astype(np.int32)
+        np.random.default_rng(0).shuffle(phys)
+        x = synth.draw_x(cfg, L.device)
+        _xp, d_offs, _d, _s = L.dispatch(x, torch.from_numpy(phys.reshape(-1, k)).to(L.device), N // k)
+        out = L.rank_offsets(d_offs)
+        torch.cuda.synchronize()
+        assert d_offs.cpu().numpy().tolist() == g["slot_offsets"]
+        assert out.cpu().numpy().tolist() == g["rank_offsets"]
+    finally:
+        L.close()

@@ -138,3 +138,28 @@ def test_removing_failed_ranks_one_at_a_time_gives_the_same_table_in_any_order()
         assert ranks == again
         live = [d for d in range(R) if d not in failed]
         assert [ranks[d] for d in live] == list(range(len(live))) and all(ranks[f] == -1 for f in failed)
+
+
+def _golden_compaction():
+    import os
+    vals = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "rank_compaction.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        key, *rest = line.split()
+        vals[key] = [int(v) for v in rest]
+    return vals
+
+
+def test_hand_worked_rank_compaction():
+    """tests/golden/rank_compaction.txt against the oracle and against the library's host code."""
+    g = _golden_compaction()
+    failed = g["rank_failed"]
+    ranks = list(range(len(failed)))
+    for d in (1, 4):                                   # in the order the fixture describes
+        ranks = orc.compact_ranks(ranks, d)
+    assert ranks == g["logical_rank"] and sum(r >= 0 for r in ranks) == g["n_live"][0]
+    assert orc.compacted_rank_offsets(g["slot_offsets"], g["logical_rank"], 2) == g["rank_offsets"]
+    import paper_2602_21140_amd as pk
+    step = pk.compact_ranks(list(range(len(failed))), 1)
+    assert pk.compact_ranks(step, 4).tolist() == g["logical_rank"]
